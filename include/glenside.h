@@ -1,0 +1,141 @@
+/*
+ * glenside.h -- C ABI of the MI355X (gfx950) evaluator for Glenside access-pattern programs.
+ *
+ * Paper: "Pure Tensor Program Rewriting via Access Patterns" (Glenside).  An access pattern
+ * (Sec. 4.1) is a dense row-major tensor of shape S_A ++ S_C viewed as an S_A-shaped tensor of
+ * S_C-shaped elements; `gs_ap` is that view: a device pointer, the shape, and the split point
+ * n_access = |S_A| (the integer of `(access T n_A)`).
+ *
+ * Conventions shared by every entry point
+ *   - Pointers inside a `gs_ap` and the `workspace` arguments are DEVICE pointers owned by the
+ *     caller.  The `gs_ap` structs themselves, and the window/stride/pad arrays, are HOST memory
+ *     and are only read during the call.  The library never allocates, frees or keeps a pointer.
+ *   - Tensors are dense and row-major over S_A ++ S_C; no strides exist at this boundary.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate on
+ *     the host, enqueue their kernels on that stream and return without synchronising.
+ *   - The return value is a `gs_status`.  Every shape rule is checked before anything is
+ *     launched, so a non-zero status other than GS_ERR_LAUNCH means nothing ran.  No exception or
+ *     abort crosses this boundary.
+ *   - Element types: GS_I8 and GS_BF16 inputs to contractions accumulate in int32 and fp32
+ *     respectively (exact for integers, no saturation; the paper's own notation is real-valued
+ *     and fixes no storage type).  bfloat16 stores round to nearest even.
+ *   - Extensions that the paper does not have are marked EXT: padding, ReLU, scaling, a fused
+ *     residual input.  With pad = 0, act = GS_ACT_NONE, scale = 1 and residual = NULL every entry
+ *     point computes exactly the paper's expression.
+ */
+#ifndef GLENSIDE_H
+#define GLENSIDE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GS_MAX_RANK 8
+
+typedef enum {
+  GS_OK = 0,
+  GS_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+  GS_ERR_RANK = 2,        /* rank / n_access / window rank do not fit the operation       */
+  GS_ERR_SHAPE = 3,       /* a shape rule of Table 1 / Table 2 is violated                */
+  GS_ERR_DTYPE = 4,       /* element types do not fit the operation                       */
+  GS_ERR_UNSUPPORTED = 5, /* valid program, but outside what the kernels cover            */
+  GS_ERR_WORKSPACE = 6,   /* workspace missing, misaligned or too small                   */
+  GS_ERR_LAUNCH = 7       /* HIP reported an error when launching                         */
+} gs_status;
+
+typedef enum { GS_I8 = 0, GS_I32 = 1, GS_BF16 = 2, GS_F32 = 3 } gs_dtype;
+typedef enum { GS_SUM = 0, GS_MAX = 1 } gs_reduce_op;
+typedef enum { GS_ACT_NONE = 0, GS_ACT_RELU = 1 } gs_activation;
+/* EXT: what a padded cell reads: zero (for dotProd / reduceSum consumers) or the lowest value of
+ * the element type (-inf for floats, the minimum integer) for reduceMax consumers.              */
+typedef enum { GS_PAD_ZERO = 0, GS_PAD_LOWEST = 1 } gs_pad_mode;
+
+typedef struct {
+  void* data;                 /* device pointer, 16-byte aligned, caller-owned               */
+  int32_t dtype;              /* gs_dtype                                                    */
+  int32_t rank;               /* |S_A| + |S_C|, at most GS_MAX_RANK                          */
+  int32_t n_access;           /* |S_A|                                                       */
+  int32_t reserved;           /* must be 0                                                   */
+  int64_t shape[GS_MAX_RANK]; /* S_A ++ S_C                                                  */
+} gs_ap;
+
+/* Human-readable name of a status code (static storage). */
+const char* glenside_status_string(int status);
+
+/* Shape rule of `windows` (Table 1): in ((a..),(b_0..b_n)), window (w_0..w_n), strides
+ * (s_0..s_n) -> out ((a.., b'_0..b'_n),(w_0..w_n)) with b'_i = ceil((b_i + lo_i + hi_i -
+ * (w_i - 1)) / s_i).  pad_lo / pad_hi (EXT) may be NULL, meaning 0.  Fills out->rank, n_access,
+ * shape and dtype; leaves out->data alone.  Host only.                                         */
+int glenside_windows_out_shape(const gs_ap* in, const int64_t* window, const int64_t* stride,
+                               const int64_t* pad_lo, const int64_t* pad_hi, gs_ap* out);
+
+/* `windows` (Table 1; element rule from the conv2d / max-pool equations of Sec. 5.1):
+ *   out[a.., p.., q..] = in[a.., p_i*s_i + q_i - lo_i ..], padded cells per pad_mode.
+ * window/stride have |S_C(in)| entries.  out must have exactly the shape the rule gives and the
+ * dtype of in (any of the four).  With in ((N),(C,H,W)), window (C,Kh,Kw), strides (1,Sh,Sw)
+ * the output, read as ((N*1*H'*W'),(C*Kh*Kw)), is the im2col matrix of Fig. 5.                   */
+int glenside_access_windows(const gs_ap* in, const int64_t* window, const int64_t* stride,
+                            const int64_t* pad_lo, const int64_t* pad_hi, int pad_mode,
+                            gs_ap* out, void* stream);
+
+/* `compute dotProd (cartProd a0 a1)` -- Fig. 2b and the left-hand side of the systolic-array
+ * rewrite (Sec. 5.2).  a0 ((m..),(k..)), a1 ((n..),(k..)) with equal compute shapes ->
+ * out ((m.., n..),()):  out[m, n] = sum_k a0[m, k] * a1[n, k].
+ * Types: i8 x i8 -> i32;  bf16 x bf16 -> f32 or bf16 (fp32 accumulate).  EXT: act applies ReLU
+ * to the result.  workspace is unused at present (pass NULL, 0).                                */
+int glenside_cartesian_dot(const gs_ap* a0, const gs_ap* a1, gs_ap* out, int act,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* 2D convolution, Fig. 2a:
+ *   (transpose (squeeze (compute dotProd (cartProd (windows (access activations 1)
+ *       (shape C Kh Kw) (shape 1 Sh Sw)) (access weights 1))) 1) (list 0 3 1 2))
+ * activations ((N),(C,H,W)), weights ((O),(C,Kh,Kw)) -> out ((N,O,H',W'),()).
+ * EXT: pad[2] symmetric zero padding of H and W; residual (may be NULL) is an access pattern of
+ * out's shape and dtype added to the result, i.e. compute reduceSum (pair conv residual);
+ * act applies ReLU last.  Types as for glenside_cartesian_dot.
+ *   _direct : the windows are formed on chip (LDS-staged patches), never written to memory.
+ *   _im2col : the rewritten program of Fig. 5: flatten(windows ...) is written to the workspace,
+ *             then contracted with flatten(weights) by the same kernel as glenside_cartesian_dot.
+ * Both need a workspace of the size their *_workspace query returns (16-byte aligned).
+ * The two forms give bit-identical integer results and float results equal up to summation
+ * order.                                                                                       */
+int glenside_conv2d_direct(const gs_ap* activations, const gs_ap* weights, const int64_t stride[2],
+                           const int64_t pad[2], const gs_ap* residual, int act, gs_ap* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+int glenside_conv2d_im2col(const gs_ap* activations, const gs_ap* weights, const int64_t stride[2],
+                           const int64_t pad[2], const gs_ap* residual, int act, gs_ap* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+/* Workspace bytes the two forms need; 0 if the arguments are invalid.  Host only. */
+size_t glenside_conv2d_direct_workspace(const gs_ap* activations, const gs_ap* weights,
+                                        const int64_t stride[2], const int64_t pad[2]);
+size_t glenside_conv2d_im2col_workspace(const gs_ap* activations, const gs_ap* weights,
+                                        const int64_t stride[2], const int64_t pad[2]);
+
+/* `compute reduceSum | reduceMax` (Table 2): in ((a..),(c..)) -> out ((a..),()).
+ * Types: i8 -> i32 (sum) or i8 (max); i32 -> i32; bf16 -> bf16 or f32; f32 -> f32.  Float sums
+ * accumulate in fp32.  EXT: scale multiplies a float result (1.0f = the paper's operator; must
+ * be 1.0f for integers and for GS_MAX).                                                         */
+int glenside_reduce(const gs_ap* in, int op, float scale, gs_ap* out, void* stream);
+
+/* `compute reduceMax|reduceSum (windows in window stride)` fused -- max pooling is Fig. 2c with
+ * in ((N,C),(H,W)).  Same result as glenside_access_windows followed by glenside_reduce, without
+ * the windows ever reaching memory.  out ((a.., b'..),()).  Padding (EXT) reads the lowest value
+ * for GS_MAX and zero for GS_SUM.  Compute rank 1..3.                                           */
+int glenside_windows_reduce(const gs_ap* in, const int64_t* window, const int64_t* stride,
+                            const int64_t* pad_lo, const int64_t* pad_hi, int op, float scale,
+                            gs_ap* out, void* stream);
+
+/* `compute reduceSum|reduceMax (pair a b)` -- the element-wise sum idiom of the blocking rewrites
+ * (Sec. 5.4): out = a + b (or max(a, b)) for patterns a, b, out of one shape ((s..),()) -- empty
+ * compute shape, since the reduction folds every compute dimension and the pair's 2 must be the
+ * only one.  EXT: act applies ReLU.  Types: a, b, out share one dtype (i32, bf16 or f32).       */
+int glenside_pair_reduce(const gs_ap* a, const gs_ap* b, int op, int act, gs_ap* out,
+                         void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLENSIDE_H */

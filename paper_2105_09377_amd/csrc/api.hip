@@ -1,0 +1,485 @@
+// C ABI of the library: host-side validation of the access-pattern shape rules (Table 1, Table 2,
+// Fig. 2, Fig. 5) and dispatch to the kernels.  Everything is checked before anything is
+// launched, so every error path can be exercised on a host without a GPU.
+#include "common.h"
+
+#include <limits.h>
+#include <string.h>
+
+using namespace gs;
+
+namespace {
+
+int64_t prod(const int64_t* v, int n) {
+  int64_t p = 1;
+  for (int i = 0; i < n; ++i) p *= v[i];
+  return p;
+}
+
+int64_t numel(const gs_ap* a) { return prod(a->shape, a->rank); }
+int64_t access_numel(const gs_ap* a) { return prod(a->shape, a->n_access); }
+int64_t compute_numel(const gs_ap* a) { return prod(a->shape + a->n_access, a->rank - a->n_access); }
+
+// Structural check of one access pattern.  `need_data` = the kernels will dereference it.
+int check_ap(const gs_ap* a, bool need_data) {
+  if (!a) return GS_ERR_NULL;
+  if (a->rank < 0 || a->rank > GS_MAX_RANK) return GS_ERR_RANK;
+  if (a->n_access < 0 || a->n_access > a->rank) return GS_ERR_RANK;
+  if (a->dtype < GS_I8 || a->dtype > GS_F32) return GS_ERR_DTYPE;
+  if (a->reserved != 0) return GS_ERR_UNSUPPORTED;
+  int64_t n = 1;
+  for (int i = 0; i < a->rank; ++i) {
+    if (a->shape[i] < 0) return GS_ERR_SHAPE;
+    if (a->shape[i] > 0 && n > (int64_t(1) << 40) / a->shape[i]) return GS_ERR_UNSUPPORTED;
+    n *= a->shape[i];
+  }
+  if (need_data && n > 0) {
+    if (!a->data) return GS_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(a->data) % 16) return GS_ERR_UNSUPPORTED;
+  }
+  return GS_OK;
+}
+
+bool same_shape(const gs_ap* a, const gs_ap* b) {
+  if (a->rank != b->rank) return false;
+  for (int i = 0; i < a->rank; ++i)
+    if (a->shape[i] != b->shape[i]) return false;
+  return true;
+}
+
+uint32_t lowest_bits(int dtype) {
+  switch (dtype) {
+    case GS_I8: return 0x80u;
+    case GS_I32: return 0x80000000u;
+    case GS_BF16: return 0xff80u;       // -inf
+    default: return 0xff800000u;        // -inf
+  }
+}
+
+int launch_status(hipError_t e) {
+  if (e == hipSuccess) return GS_OK;
+  if (e == hipErrorInvalidValue) return GS_ERR_UNSUPPORTED;
+  return GS_ERR_LAUNCH;
+}
+
+// Shape rule of `windows` with optional padding.  Fills dims of the result.
+int windows_shape(const gs_ap* in, const int64_t* window, const int64_t* stride,
+                  const int64_t* pad_lo, const int64_t* pad_hi, gs_ap* out) {
+  int st = check_ap(in, false);
+  if (st) return st;
+  if (!window || !stride || !out) return GS_ERR_NULL;
+  const int nc = in->rank - in->n_access;
+  if (nc < 1) return GS_ERR_RANK;
+  if (in->rank + nc > GS_MAX_RANK) return GS_ERR_RANK;
+  out->dtype = in->dtype;
+  out->rank = in->rank + nc;
+  out->n_access = in->n_access + nc;
+  out->reserved = 0;
+  for (int i = 0; i < in->n_access; ++i) out->shape[i] = in->shape[i];
+  for (int d = 0; d < nc; ++d) {
+    const int64_t lo = pad_lo ? pad_lo[d] : 0, hi = pad_hi ? pad_hi[d] : 0;
+    const int64_t b = in->shape[in->n_access + d] + lo + hi;
+    if (lo < 0 || hi < 0 || window[d] < 1 || stride[d] < 1 || window[d] > b) return GS_ERR_SHAPE;
+    out->shape[in->n_access + d] = ceil_div(b - (window[d] - 1), stride[d]);
+    out->shape[in->n_access + nc + d] = window[d];
+  }
+  return GS_OK;
+}
+
+struct ConvShape {
+  int N, C, H, W, O, Kh, Kw, Sh, Sw, Ph, Pw, Ho, Wo;
+};
+
+int conv_shape(const gs_ap* act, const gs_ap* w, const int64_t* stride, const int64_t* pad,
+               ConvShape* cs) {
+  int st = check_ap(act, false);
+  if (st) return st;
+  st = check_ap(w, false);
+  if (st) return st;
+  if (!stride || !pad) return GS_ERR_NULL;
+  if (act->rank != 4 || act->n_access != 1 || w->rank != 4 || w->n_access != 1) return GS_ERR_RANK;
+  if (act->dtype != w->dtype) return GS_ERR_DTYPE;
+  if (act->dtype != GS_I8 && act->dtype != GS_BF16) return GS_ERR_DTYPE;
+  for (int i = 0; i < 4; ++i)
+    if (act->shape[i] > INT_MAX / 4 || w->shape[i] > INT_MAX / 4) return GS_ERR_UNSUPPORTED;
+  if (act->shape[1] != w->shape[1]) return GS_ERR_SHAPE;   // window covers all C channels
+  if (stride[0] < 1 || stride[1] < 1 || pad[0] < 0 || pad[1] < 0) return GS_ERR_SHAPE;
+  if (stride[0] > 64 || stride[1] > 64 || pad[0] > 64 || pad[1] > 64) return GS_ERR_UNSUPPORTED;
+  cs->N = int(act->shape[0]); cs->C = int(act->shape[1]);
+  cs->H = int(act->shape[2]); cs->W = int(act->shape[3]);
+  cs->O = int(w->shape[0]); cs->Kh = int(w->shape[2]); cs->Kw = int(w->shape[3]);
+  cs->Sh = int(stride[0]); cs->Sw = int(stride[1]); cs->Ph = int(pad[0]); cs->Pw = int(pad[1]);
+  if (cs->C < 1 || cs->Kh < 1 || cs->Kw < 1) return GS_ERR_SHAPE;
+  if (cs->Kh > cs->H + 2 * cs->Ph || cs->Kw > cs->W + 2 * cs->Pw) return GS_ERR_SHAPE;
+  cs->Ho = (cs->H + 2 * cs->Ph - cs->Kh) / cs->Sh + 1;
+  cs->Wo = (cs->W + 2 * cs->Pw - cs->Kw) / cs->Sw + 1;
+  if (int64_t(cs->N) * cs->O * cs->Ho * cs->Wo >= (int64_t(1) << 31)) return GS_ERR_UNSUPPORTED;
+  if (int64_t(cs->N) * cs->C * cs->H * cs->W >= (int64_t(1) << 31)) return GS_ERR_UNSUPPORTED;
+  return GS_OK;
+}
+
+int conv_check_io(const gs_ap* act, const gs_ap* w, const gs_ap* residual, int actfn,
+                  const gs_ap* out, const ConvShape& cs) {
+  int st = check_ap(act, true);
+  if (st) return st;
+  st = check_ap(w, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if (actfn != GS_ACT_NONE && actfn != GS_ACT_RELU) return GS_ERR_UNSUPPORTED;
+  if (out->rank != 4 || out->n_access != 4) return GS_ERR_RANK;
+  const int64_t want[4] = {cs.N, cs.O, cs.Ho, cs.Wo};
+  for (int i = 0; i < 4; ++i)
+    if (out->shape[i] != want[i]) return GS_ERR_SHAPE;
+  if (act->dtype == GS_I8 ? out->dtype != GS_I32
+                          : (out->dtype != GS_F32 && out->dtype != GS_BF16))
+    return GS_ERR_DTYPE;
+  if (residual) {
+    st = check_ap(residual, true);
+    if (st) return st;
+    if (!same_shape(residual, out)) return GS_ERR_SHAPE;
+    if (residual->dtype != out->dtype) return GS_ERR_DTYPE;
+  }
+  return GS_OK;
+}
+
+int64_t im2col_ld(int dtype, int64_t K) { return round_up(K, 16 / int64_t(dtype_size(dtype))); }
+
+}  // namespace
+
+extern "C" {
+
+const char* glenside_status_string(int status) {
+  switch (status) {
+    case GS_OK: return "ok";
+    case GS_ERR_NULL: return "null pointer";
+    case GS_ERR_RANK: return "rank or access split does not fit the operation";
+    case GS_ERR_SHAPE: return "shape rule violated";
+    case GS_ERR_DTYPE: return "element types do not fit the operation";
+    case GS_ERR_UNSUPPORTED: return "valid program outside what the kernels cover";
+    case GS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GS_ERR_LAUNCH: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int glenside_windows_out_shape(const gs_ap* in, const int64_t* window, const int64_t* stride,
+                               const int64_t* pad_lo, const int64_t* pad_hi, gs_ap* out) {
+  return windows_shape(in, window, stride, pad_lo, pad_hi, out);
+}
+
+int glenside_access_windows(const gs_ap* in, const int64_t* window, const int64_t* stride,
+                            const int64_t* pad_lo, const int64_t* pad_hi, int pad_mode,
+                            gs_ap* out, void* stream) {
+  gs_ap want;
+  int st = windows_shape(in, window, stride, pad_lo, pad_hi, &want);
+  if (st) return st;
+  if (pad_mode != GS_PAD_ZERO && pad_mode != GS_PAD_LOWEST) return GS_ERR_UNSUPPORTED;
+  st = check_ap(in, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if (out->rank != want.rank || out->n_access != want.n_access) return GS_ERR_RANK;
+  if (!same_shape(out, &want)) return GS_ERR_SHAPE;
+  if (out->dtype != in->dtype) return GS_ERR_DTYPE;
+  const int nc = in->rank - in->n_access;
+  if (nc > 4) return GS_ERR_UNSUPPORTED;
+  WindowsArgs a;
+  memset(&a, 0, sizeof(a));
+  a.in = in->data;
+  a.out = out->data;
+  a.esz = int(dtype_size(in->dtype));
+  a.n_compute = nc;
+  a.outer = access_numel(in);
+  int64_t k = 1;
+  for (int d = 0; d < nc; ++d) {
+    a.in_dim[d] = in->shape[in->n_access + d];
+    a.out_dim[d] = want.shape[in->n_access + d];
+    a.win[d] = window[d];
+    a.stride[d] = stride[d];
+    a.pad_lo[d] = pad_lo ? pad_lo[d] : 0;
+    k *= window[d];
+  }
+  a.fill_bits = pad_mode == GS_PAD_LOWEST ? lowest_bits(in->dtype) : 0u;
+  a.out_row_stride = k;
+  return launch_status(launch_windows(a, static_cast<hipStream_t>(stream)));
+}
+
+int glenside_cartesian_dot(const gs_ap* a0, const gs_ap* a1, gs_ap* out, int act, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int st = check_ap(a0, true);
+  if (st) return st;
+  st = check_ap(a1, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if (act != GS_ACT_NONE && act != GS_ACT_RELU) return GS_ERR_UNSUPPORTED;
+  // cartProd: compute shapes must be equal (Table 1).
+  const int nc0 = a0->rank - a0->n_access, nc1 = a1->rank - a1->n_access;
+  if (nc0 != nc1) return GS_ERR_SHAPE;
+  for (int d = 0; d < nc0; ++d)
+    if (a0->shape[a0->n_access + d] != a1->shape[a1->n_access + d]) return GS_ERR_SHAPE;
+  // Result ((m.., n..), ()).
+  if (out->rank != a0->n_access + a1->n_access || out->n_access != out->rank) return GS_ERR_RANK;
+  for (int d = 0; d < a0->n_access; ++d)
+    if (out->shape[d] != a0->shape[d]) return GS_ERR_SHAPE;
+  for (int d = 0; d < a1->n_access; ++d)
+    if (out->shape[a0->n_access + d] != a1->shape[d]) return GS_ERR_SHAPE;
+  if (a0->dtype != a1->dtype) return GS_ERR_DTYPE;
+  if (a0->dtype == GS_I8) {
+    if (out->dtype != GS_I32) return GS_ERR_DTYPE;
+  } else if (a0->dtype == GS_BF16) {
+    if (out->dtype != GS_F32 && out->dtype != GS_BF16) return GS_ERR_DTYPE;
+  } else {
+    return GS_ERR_DTYPE;
+  }
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.x = a0->data;
+  g.y = a1->data;
+  g.out = out->data;
+  g.in_dtype = a0->dtype;
+  g.out_dtype = out->dtype;
+  g.I = access_numel(a0);
+  g.J = access_numel(a1);
+  g.K = compute_numel(a0);
+  g.ldx = g.ldy = g.K;
+  g.jp = g.J > 0 ? g.J : 1;
+  g.relu = act == GS_ACT_RELU;
+  return launch_status(launch_gemm(g, static_cast<hipStream_t>(stream)));
+}
+
+size_t glenside_conv2d_direct_workspace(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                                        const int64_t pad[2]) {
+  ConvShape cs;
+  if (conv_shape(act, w, stride, pad, &cs)) return 0;
+  return round_up(int64_t(conv_weight_workspace(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw)), 256) + 256;
+}
+
+size_t glenside_conv2d_im2col_workspace(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                                        const int64_t pad[2]) {
+  ConvShape cs;
+  if (conv_shape(act, w, stride, pad, &cs)) return 0;
+  const int64_t esz = int64_t(dtype_size(act->dtype));
+  const int64_t K = int64_t(cs.C) * cs.Kh * cs.Kw, ld = im2col_ld(act->dtype, K);
+  const int64_t M = int64_t(cs.N) * cs.Ho * cs.Wo;
+  return size_t(round_up(M * ld * esz, 256) + round_up(int64_t(cs.O) * ld * esz, 256) + 256);
+}
+
+int glenside_conv2d_direct(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                           const int64_t pad[2], const gs_ap* residual, int actfn, gs_ap* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  ConvShape cs;
+  int st = conv_shape(act, w, stride, pad, &cs);
+  if (st) return st;
+  st = conv_check_io(act, w, residual, actfn, out, cs);
+  if (st) return st;
+  const size_t need = glenside_conv2d_direct_workspace(act, w, stride, pad);
+  if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16)
+    return GS_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_conv_repack(w->data, workspace, act->dtype, cs.O, cs.C, cs.Kh, cs.Kw, s);
+  if (e != hipSuccess) return launch_status(e);
+  ConvArgs a;
+  memset(&a, 0, sizeof(a));
+  a.act = act->data;
+  a.wr = workspace;
+  a.out = out->data;
+  a.residual = residual ? residual->data : nullptr;
+  a.in_dtype = act->dtype;
+  a.out_dtype = out->dtype;
+  a.N = cs.N; a.C = cs.C; a.H = cs.H; a.W = cs.W; a.O = cs.O; a.Kh = cs.Kh; a.Kw = cs.Kw;
+  a.Sh = cs.Sh; a.Sw = cs.Sw; a.Ph = cs.Ph; a.Pw = cs.Pw; a.Ho = cs.Ho; a.Wo = cs.Wo;
+  a.Cpad = int(conv_weight_workspace(act->dtype, 1, cs.C, 1, 1) / dtype_size(act->dtype));
+  a.relu = actfn == GS_ACT_RELU;
+  return launch_status(launch_conv(a, s));
+}
+
+int glenside_conv2d_im2col(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                           const int64_t pad[2], const gs_ap* residual, int actfn, gs_ap* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  ConvShape cs;
+  int st = conv_shape(act, w, stride, pad, &cs);
+  if (st) return st;
+  st = conv_check_io(act, w, residual, actfn, out, cs);
+  if (st) return st;
+  const size_t need = glenside_conv2d_im2col_workspace(act, w, stride, pad);
+  if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16)
+    return GS_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t esz = int64_t(dtype_size(act->dtype));
+  const int64_t K = int64_t(cs.C) * cs.Kh * cs.Kw, ld = im2col_ld(act->dtype, K);
+  const int64_t M = int64_t(cs.N) * cs.Ho * cs.Wo;
+  uint8_t* cols = static_cast<uint8_t*>(workspace);
+  uint8_t* wpad = cols + round_up(M * ld * esz, 256);
+
+  // flatten (windows (access activations 1) (C Kh Kw) (1 Sh Sw)), rows padded to 16 bytes.
+  WindowsArgs wa;
+  memset(&wa, 0, sizeof(wa));
+  wa.in = act->data;
+  wa.out = cols;
+  wa.esz = int(esz);
+  wa.n_compute = 3;
+  wa.outer = cs.N;
+  const int64_t in_dim[3] = {cs.C, cs.H, cs.W}, out_dim[3] = {1, cs.Ho, cs.Wo};
+  const int64_t win[3] = {cs.C, cs.Kh, cs.Kw}, str[3] = {1, cs.Sh, cs.Sw}, plo[3] = {0, cs.Ph, cs.Pw};
+  for (int d = 0; d < 3; ++d) {
+    wa.in_dim[d] = in_dim[d]; wa.out_dim[d] = out_dim[d]; wa.win[d] = win[d];
+    wa.stride[d] = str[d]; wa.pad_lo[d] = plo[d];
+  }
+  wa.fill_bits = 0;
+  wa.out_row_stride = ld;
+  hipError_t e = launch_windows(wa, s);
+  if (e != hipSuccess) return launch_status(e);
+
+  // flatten (access weights 1): already ((O),(K)) in memory; copied only when rows need padding.
+  const void* wmat = w->data;
+  if (ld != K) {
+    WindowsArgs ww;
+    memset(&ww, 0, sizeof(ww));
+    ww.in = w->data;
+    ww.out = wpad;
+    ww.esz = int(esz);
+    ww.n_compute = 1;
+    ww.outer = cs.O;
+    ww.in_dim[0] = K; ww.out_dim[0] = 1; ww.win[0] = K; ww.stride[0] = 1; ww.pad_lo[0] = 0;
+    ww.out_row_stride = ld;
+    e = launch_windows(ww, s);
+    if (e != hipSuccess) return launch_status(e);
+    wmat = wpad;
+  }
+
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.x = wmat;
+  g.y = cols;
+  g.out = out->data;
+  g.residual = residual ? residual->data : nullptr;
+  g.in_dtype = act->dtype;
+  g.out_dtype = out->dtype;
+  g.I = cs.O;
+  g.J = M;
+  g.K = K;
+  g.ldx = g.ldy = ld;
+  g.jp = int64_t(cs.Ho) * cs.Wo;
+  if (g.jp < 1) g.jp = 1;
+  g.relu = actfn == GS_ACT_RELU;
+  return launch_status(launch_gemm(g, s));
+}
+
+int glenside_reduce(const gs_ap* in, int op, float scale, gs_ap* out, void* stream) {
+  int st = check_ap(in, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if (op != GS_SUM && op != GS_MAX) return GS_ERR_UNSUPPORTED;
+  if (out->rank != in->n_access || out->n_access != out->rank) return GS_ERR_RANK;
+  for (int d = 0; d < out->rank; ++d)
+    if (out->shape[d] != in->shape[d]) return GS_ERR_SHAPE;
+  const bool is_int = in->dtype == GS_I8 || in->dtype == GS_I32;
+  if (in->dtype == GS_I8) {
+    if (out->dtype != (op == GS_SUM ? GS_I32 : GS_I8)) return GS_ERR_DTYPE;
+  } else if (in->dtype == GS_I32) {
+    if (out->dtype != GS_I32) return GS_ERR_DTYPE;
+  } else if (in->dtype == GS_BF16) {
+    if (out->dtype != GS_BF16 && out->dtype != GS_F32) return GS_ERR_DTYPE;
+  } else {
+    if (out->dtype != GS_F32) return GS_ERR_DTYPE;
+  }
+  if ((is_int || op == GS_MAX) && scale != 1.0f) return GS_ERR_UNSUPPORTED;
+  const int64_t cols = compute_numel(in);
+  if (op == GS_MAX && cols == 0 && access_numel(in) > 0) return GS_ERR_SHAPE;   // max of nothing
+  ReduceArgs a;
+  memset(&a, 0, sizeof(a));
+  a.in = in->data;
+  a.out = out->data;
+  a.in_dtype = in->dtype;
+  a.out_dtype = out->dtype;
+  a.op = op;
+  a.rows = access_numel(in);
+  a.cols = cols;
+  a.scale = scale;
+  return launch_status(launch_reduce(a, static_cast<hipStream_t>(stream)));
+}
+
+int glenside_windows_reduce(const gs_ap* in, const int64_t* window, const int64_t* stride,
+                            const int64_t* pad_lo, const int64_t* pad_hi, int op, float scale,
+                            gs_ap* out, void* stream) {
+  gs_ap win;
+  int st = windows_shape(in, window, stride, pad_lo, pad_hi, &win);
+  if (st) return st;
+  st = check_ap(in, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if (op != GS_SUM && op != GS_MAX) return GS_ERR_UNSUPPORTED;
+  const int nc = in->rank - in->n_access;
+  if (nc > 3) return GS_ERR_UNSUPPORTED;
+  // compute reduce (windows ...): ((a.., b'..), ()).
+  if (out->rank != win.n_access || out->n_access != out->rank) return GS_ERR_RANK;
+  for (int d = 0; d < out->rank; ++d)
+    if (out->shape[d] != win.shape[d]) return GS_ERR_SHAPE;
+  const bool is_int = in->dtype == GS_I8 || in->dtype == GS_I32;
+  if (in->dtype == GS_I8) {
+    if (out->dtype != (op == GS_SUM ? GS_I32 : GS_I8)) return GS_ERR_DTYPE;
+  } else if (in->dtype == GS_I32) {
+    if (out->dtype != GS_I32) return GS_ERR_DTYPE;
+  } else if (in->dtype == GS_BF16) {
+    if (out->dtype != GS_BF16 && out->dtype != GS_F32) return GS_ERR_DTYPE;
+  } else {
+    if (out->dtype != GS_F32) return GS_ERR_DTYPE;
+  }
+  if ((is_int || op == GS_MAX) && scale != 1.0f) return GS_ERR_UNSUPPORTED;
+  WindowsReduceArgs a;
+  memset(&a, 0, sizeof(a));
+  a.in = in->data;
+  a.out = out->data;
+  a.in_dtype = in->dtype;
+  a.out_dtype = out->dtype;
+  a.op = op;
+  a.n_compute = nc;
+  a.outer = access_numel(in);
+  for (int d = 0; d < nc; ++d) {
+    a.in_dim[d] = in->shape[in->n_access + d];
+    a.out_dim[d] = win.shape[in->n_access + d];
+    a.win[d] = window[d];
+    a.stride[d] = stride[d];
+    a.pad_lo[d] = pad_lo ? pad_lo[d] : 0;
+  }
+  a.scale = scale;
+  return launch_status(launch_windows_reduce(a, static_cast<hipStream_t>(stream)));
+}
+
+int glenside_pair_reduce(const gs_ap* a, const gs_ap* b, int op, int act, gs_ap* out,
+                         void* stream) {
+  int st = check_ap(a, true);
+  if (st) return st;
+  st = check_ap(b, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if (op != GS_SUM && op != GS_MAX) return GS_ERR_UNSUPPORTED;
+  if (act != GS_ACT_NONE && act != GS_ACT_RELU) return GS_ERR_UNSUPPORTED;
+  // pair needs two patterns of one shape (Table 1).  reduceSum then folds every compute
+  // dimension, so the result is element-wise only for patterns with empty compute shape.
+  if (a->rank != b->rank || a->n_access != b->n_access) return GS_ERR_RANK;
+  if (a->n_access != a->rank || out->n_access != out->rank) return GS_ERR_RANK;
+  if (!same_shape(a, b)) return GS_ERR_SHAPE;
+  if (out->rank != a->rank) return GS_ERR_RANK;
+  if (!same_shape(a, out)) return GS_ERR_SHAPE;
+  if (a->dtype != b->dtype || a->dtype != out->dtype || a->dtype == GS_I8) return GS_ERR_DTYPE;
+  PairArgs p;
+  memset(&p, 0, sizeof(p));
+  p.a = a->data;
+  p.b = b->data;
+  p.out = out->data;
+  p.dtype = a->dtype;
+  p.op = op;
+  p.relu = act == GS_ACT_RELU;
+  p.n = numel(a);
+  return launch_status(launch_pair_reduce(p, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+// Shared device/host helpers for the gfx950 kernels: element types, conversions, MFMA traits.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/glenside.h"
+
+namespace gs {
+
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kWave = 64;
+
+__host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+__host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+__host__ __device__ inline size_t dtype_size(int dt) {
+  return dt == GS_I8 ? 1 : dt == GS_BF16 ? 2 : 4;
+}
+
+// bfloat16 is the upper half of an IEEE binary32.
+__device__ inline float bf16_bits_to_float(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
+
+// Round to nearest, ties to even; NaN stays a quiet NaN.
+__device__ inline uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+// Element-type traits for the two contraction flavours.  One MFMA consumes 32 bytes of K per
+// row: lanes 0-31 supply bytes [0,16), lanes 32-63 bytes [16,32) of the K step, for row/column
+// (lane % 32).  The 32x32 result has column (lane % 32) and rows 8*(v/4) + 4*(lane/32) + v%4 in
+// accumulator register v.
+struct Bf16Traits {
+  using acc_t = float;
+  using accv_t = f32x16;
+  static constexpr int kEsz = 2;
+  __device__ static inline accv_t mfma(const i32x4& a, const i32x4& b, const accv_t& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+
+struct I8Traits {
+  using acc_t = int32_t;
+  using accv_t = i32x16;
+  static constexpr int kEsz = 1;
+  __device__ static inline accv_t mfma(const i32x4& a, const i32x4& b, const accv_t& c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+  }
+};
+
+// Epilogue shared by the contractions: optional residual, optional ReLU, store in the output
+// type.  `addr` is an element offset.
+template <typename AccT>
+__device__ inline void store_result(void* out, const void* residual, int out_dtype, int64_t addr,
+                                    AccT v, int relu) {
+  if constexpr (sizeof(AccT) == 4 && __is_same(AccT, int32_t)) {
+    int32_t r = v;
+    if (residual) r += static_cast<const int32_t*>(residual)[addr];
+    if (relu) r = r > 0 ? r : 0;
+    static_cast<int32_t*>(out)[addr] = r;
+  } else {
+    float r = v;
+    if (out_dtype == GS_F32) {
+      if (residual) r += static_cast<const float*>(residual)[addr];
+      if (relu) r = fmaxf(r, 0.0f);
+      static_cast<float*>(out)[addr] = r;
+    } else {
+      if (residual) r += bf16_bits_to_float(static_cast<const uint16_t*>(residual)[addr]);
+      if (relu) r = fmaxf(r, 0.0f);
+      static_cast<uint16_t*>(out)[addr] = float_to_bf16_bits(r);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel launchers (defined in the .hip files).  All return hipError_t from the launch.
+// ---------------------------------------------------------------------------------------------
+
+struct WindowsArgs {      // generic N-d windows over the compute dims
+  const void* in;
+  void* out;
+  int esz;                // element size in bytes
+  int n_compute;          // number of windowed dims (1..4)
+  int64_t outer;          // product of the access dims of `in`
+  int64_t in_dim[4];      // b_i
+  int64_t out_dim[4];     // b'_i
+  int64_t win[4];         // w_i
+  int64_t stride[4];
+  int64_t pad_lo[4];
+  uint32_t fill_bits;     // padded-cell value, in the low esz bytes
+  int64_t out_row_stride; // elements between consecutive windows in `out` (>= prod w_i)
+};
+hipError_t launch_windows(const WindowsArgs& a, hipStream_t s);
+
+struct GemmArgs {         // C[i][j] = sum_k X[i][k] * Y[j][k]
+  const void* x;          // I x K, row stride ldx elements
+  const void* y;          // J x K, row stride ldy elements
+  void* out;
+  const void* residual;   // same addressing as out, may be null
+  int in_dtype;           // GS_I8 or GS_BF16
+  int out_dtype;
+  int64_t I, J, K, ldx, ldy;
+  int64_t jp;             // out element offset = (j / jp) * (I * jp) + i * jp + (j % jp)
+  int relu;
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+struct ConvArgs {
+  const void* act;        // N x C x H x W
+  const void* wr;         // repacked weights: O x (Kh*Kw) x Cpad, channel fastest, zero padded
+  void* out;              // N x O x Ho x Wo
+  const void* residual;
+  int in_dtype, out_dtype;
+  int N, C, H, W, O, Kh, Kw, Sh, Sw, Ph, Pw, Ho, Wo;
+  int Cpad;               // channels per tap in `wr`
+  int relu;
+};
+size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw);
+hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int C, int Kh, int Kw,
+                              hipStream_t s);
+// Returns hipErrorInvalidValue if no tile configuration fits the LDS for this shape.
+hipError_t launch_conv(const ConvArgs& a, hipStream_t s);
+
+struct ReduceArgs {       // out[r] = reduce over `cols` contiguous values
+  const void* in;
+  void* out;
+  int in_dtype, out_dtype, op;
+  int64_t rows, cols;
+  float scale;
+};
+hipError_t launch_reduce(const ReduceArgs& a, hipStream_t s);
+
+struct WindowsReduceArgs {
+  const void* in;
+  void* out;
+  int in_dtype, out_dtype, op;
+  int n_compute;          // 1..3
+  int64_t outer;
+  int64_t in_dim[3], out_dim[3], win[3], stride[3], pad_lo[3];
+  float scale;
+};
+hipError_t launch_windows_reduce(const WindowsReduceArgs& a, hipStream_t s);
+
+struct PairArgs {
+  const void* a;
+  const void* b;
+  void* out;
+  int dtype, op, relu;
+  int64_t n;
+};
+hipError_t launch_pair_reduce(const PairArgs& a, hipStream_t s);
+
+}  // namespace gs

@@ -1,0 +1,56 @@
+"""Shared helpers for the tests: torch <-> oracle value conversion and the parity metrics."""
+
+import numpy as np
+import torch
+
+from oracle import numerics
+
+
+def to_oracle(t: torch.Tensor) -> np.ndarray:
+    """Exact values of a tensor as int64 / float64 (bfloat16 goes through its bit pattern)."""
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        bits = t.view(torch.int16).numpy().view(np.uint16)
+        return numerics.bf16_bits_to_f64(bits)
+    if t.dtype in (torch.int8, torch.int32, torch.int64):
+        return t.numpy().astype(np.int64)
+    return t.numpy().astype(np.float64)
+
+
+def expected_storage(ref: np.ndarray, dtype: torch.dtype) -> np.ndarray:
+    """Round an oracle result (int64 / float64) to the storage type of the GPU output."""
+    if dtype == torch.int32:
+        return numerics.to_i32_checked(ref).astype(np.int64)
+    if dtype == torch.int8:
+        assert ref.min() >= -128 and ref.max() <= 127
+        return ref.astype(np.int64)
+    if dtype == torch.float32:
+        return numerics.round_to_f32(ref).astype(np.float64)
+    if dtype == torch.bfloat16:
+        return numerics.round_to_bf16_value(ref)
+    raise TypeError(dtype)
+
+
+def rel_error(got: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |g_i - r_i| / max(|r_i|, 1e-3 * max|r|): relative error with a floor for outputs near zero."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    floor = 1e-3 * np.abs(ref).max()
+    denom = np.maximum(np.abs(ref), max(floor, 1e-30))
+    return float((np.abs(got - ref) / denom).max())
+
+
+def assert_parity(got_t: torch.Tensor, ref: np.ndarray, float_tol: float = 1e-2, what: str = ""):
+    """Bit-exact for integer outputs; max relative error <= float_tol for float outputs."""
+    got = to_oracle(got_t)
+    want = expected_storage(ref, got_t.dtype)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    if got_t.dtype in (torch.int8, torch.int32):
+        bad = np.nonzero(got != want)
+        assert bad[0].size == 0, f"{what}: {bad[0].size} integer mismatches, first at {[b[0] for b in bad]}"
+    else:
+        assert np.isfinite(got).all() or not np.isfinite(want).all(), what + ": non-finite output"
+        err = rel_error(got, want)
+        assert err <= float_tol, f"{what}: max relative error {err:.3e} > {float_tol}"

@@ -1,0 +1,137 @@
+"""The C ABI without a GPU: the library loads, exports what the header declares, and rejects bad
+arguments on the host before anything is launched."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2105_09377_amd import binding as gs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000   # aligned, non-null, never dereferenced: validation fails first in every test
+
+
+def ap(shape, n_access, dtype=gs.GS_BF16, data=FAKE):
+    a = gs.gs_ap()
+    a.data, a.dtype, a.rank, a.n_access, a.reserved = data, dtype, len(shape), n_access, 0
+    for i, s in enumerate(shape):
+        a.shape[i] = s
+    return a
+
+
+def i64(*v):
+    return (ctypes.c_int64 * len(v))(*v)
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "glenside.h")) as fh:
+        header = fh.read()
+    declared = set(re.findall(r"\b(glenside_\w+)\s*\(", header))
+    assert declared == set(gs.EXPORTS)
+    lib = gs.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    assert gs.status_string(gs.GS_OK) == "ok"
+    assert "shape" in gs.status_string(gs.GS_ERR_SHAPE)
+    assert "unknown" in gs.status_string(99)
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(gs.gs_ap) == 8 + 4 * 4 + 8 * gs.GS_MAX_RANK
+    assert gs.gs_ap.shape.offset == 24
+
+
+@pytest.mark.parametrize("shape,na,window,stride,lo,hi,want", [
+    ((2, 3, 8, 9), 1, (3, 3, 2), (1, 1, 2), None, None, ((2, 1, 6, 4, 3, 3, 2), 4)),
+    ((32, 64, 56, 56), 1, (64, 3, 3), (1, 1, 1), (0, 1, 1), (0, 1, 1), ((32, 1, 56, 56, 64, 3, 3), 4)),
+    ((64, 64, 112, 112), 2, (3, 3), (2, 2), (1, 1), (1, 1), ((64, 64, 56, 56, 3, 3), 4)),
+    ((5, 10), 1, (4,), (3,), None, None, ((5, 3, 4), 2)),
+])
+def test_windows_shape_rule(shape, na, window, stride, lo, hi, want):
+    assert gs.windows_out_shape(shape, na, window, stride, lo, hi) == want
+
+
+def test_windows_shape_errors():
+    with pytest.raises(gs.GlensideError) as e:
+        gs.windows_out_shape((2, 8), 1, (9,), (1,))          # window larger than the dimension
+    assert e.value.status == gs.GS_ERR_SHAPE
+    with pytest.raises(gs.GlensideError) as e:
+        gs.windows_out_shape((2, 8), 2, (3,), (1,))          # no compute dimension to window
+    assert e.value.status == gs.GS_ERR_RANK
+    with pytest.raises(gs.GlensideError) as e:
+        gs.windows_out_shape((2, 8), 1, (3,), (0,))          # stride 0
+    assert e.value.status == gs.GS_ERR_SHAPE
+
+
+def test_cartesian_dot_validation():
+    L = gs.lib()
+    call = lambda a0, a1, out, act=0: L.glenside_cartesian_dot(ctypes.byref(a0), ctypes.byref(a1),
+                                                               ctypes.byref(out), act, None, 0, None)
+    good0, good1 = ap((4, 16), 1), ap((8, 16), 1)
+    assert call(good0, ap((8, 15), 1), ap((4, 8), 2, gs.GS_F32)) == gs.GS_ERR_SHAPE      # compute dims differ
+    assert call(good0, good1, ap((4, 9), 2, gs.GS_F32)) == gs.GS_ERR_SHAPE               # wrong result shape
+    assert call(good0, good1, ap((4, 8), 1, gs.GS_F32)) == gs.GS_ERR_RANK                # result must be all-access
+    assert call(good0, good1, ap((4, 8), 2, gs.GS_I32)) == gs.GS_ERR_DTYPE               # bf16 -> i32
+    assert call(good0, ap((8, 16), 1, gs.GS_I8), ap((4, 8), 2, gs.GS_F32)) == gs.GS_ERR_DTYPE
+    assert call(good0, good1, ap((4, 8), 2, gs.GS_F32), act=7) == gs.GS_ERR_UNSUPPORTED
+    assert call(ap((4, 16), 1, data=0), good1, ap((4, 8), 2, gs.GS_F32)) == gs.GS_ERR_NULL
+    assert call(ap((4, 16), 1, data=FAKE + 2), good1, ap((4, 8), 2, gs.GS_F32)) == gs.GS_ERR_UNSUPPORTED
+    assert L.glenside_cartesian_dot(None, ctypes.byref(good1), ctypes.byref(good1), 0, None, 0, None) == gs.GS_ERR_NULL
+    bad_rank = ap((4, 16), 1)
+    bad_rank.rank = 9
+    assert call(bad_rank, good1, ap((4, 8), 2, gs.GS_F32)) == gs.GS_ERR_RANK
+
+
+def test_conv_validation_and_workspace_queries():
+    L = gs.lib()
+    x, w = ap((2, 3, 8, 8), 1, gs.GS_I8), ap((4, 3, 3, 3), 1, gs.GS_I8)
+    st, pd = i64(1, 1), i64(0, 0)
+    out = ap((2, 4, 6, 6), 4, gs.GS_I32)
+    for fn in (L.glenside_conv2d_direct, L.glenside_conv2d_im2col):
+        call = lambda x_, w_, out_, ws=FAKE, nbytes=1 << 30, res=None: fn(
+            ctypes.byref(x_), ctypes.byref(w_), st, pd, res, 0, ctypes.byref(out_), ws, nbytes, None)
+        assert call(x, ap((4, 2, 3, 3), 1, gs.GS_I8), out) == gs.GS_ERR_SHAPE       # channel mismatch
+        assert call(x, w, ap((2, 4, 6, 5), 4, gs.GS_I32)) == gs.GS_ERR_SHAPE         # wrong H'/W'
+        assert call(x, w, ap((2, 4, 6, 6), 4, gs.GS_F32)) == gs.GS_ERR_DTYPE         # i8 must give i32
+        assert call(ap((2, 3, 8, 8), 2, gs.GS_I8), w, out) == gs.GS_ERR_RANK         # activations are (access x 1)
+        assert call(x, ap((4, 3, 9, 3), 1, gs.GS_I8), out) == gs.GS_ERR_SHAPE        # window taller than the image
+        assert call(x, w, out, ws=None) == gs.GS_ERR_WORKSPACE
+        assert call(x, w, out, nbytes=8) == gs.GS_ERR_WORKSPACE
+        assert call(x, w, out, res=ctypes.byref(ap((2, 4, 6, 6), 4, gs.GS_F32))) == gs.GS_ERR_DTYPE
+    d = L.glenside_conv2d_direct_workspace(ctypes.byref(x), ctypes.byref(w), st, pd)
+    m = L.glenside_conv2d_im2col_workspace(ctypes.byref(x), ctypes.byref(w), st, pd)
+    assert d >= 4 * 9 * 32                      # repacked weights, channels padded to a 32-byte step
+    assert m >= 2 * 36 * 32                     # 72 windows of 27 int8, rows padded to 32 bytes
+    assert L.glenside_conv2d_direct_workspace(ctypes.byref(x), ctypes.byref(ap((4, 2, 3, 3), 1, gs.GS_I8)), st, pd) == 0
+
+
+def test_reduce_and_pair_validation():
+    L = gs.lib()
+    red = lambda a, op, scale, out: L.glenside_reduce(ctypes.byref(a), op, ctypes.c_float(scale), ctypes.byref(out), None)
+    x = ap((4, 5, 7, 7), 2)
+    assert red(x, gs.GS_SUM, 1.0, ap((4, 6), 2)) == gs.GS_ERR_SHAPE
+    assert red(x, gs.GS_SUM, 1.0, ap((4, 5, 1), 3)) == gs.GS_ERR_RANK
+    assert red(x, 5, 1.0, ap((4, 5), 2)) == gs.GS_ERR_UNSUPPORTED
+    assert red(x, gs.GS_MAX, 0.5, ap((4, 5), 2)) == gs.GS_ERR_UNSUPPORTED            # scale only for float sums
+    assert red(ap((4, 5, 7, 7), 2, gs.GS_I8), gs.GS_SUM, 1.0, ap((4, 5), 2, gs.GS_I8)) == gs.GS_ERR_DTYPE
+    assert red(ap((4, 0), 1), gs.GS_MAX, 1.0, ap((4,), 1)) == gs.GS_ERR_SHAPE        # max of an empty element
+    pr = lambda a, b, out: L.glenside_pair_reduce(ctypes.byref(a), ctypes.byref(b), 0, 0, ctypes.byref(out), None)
+    y = ap((4, 5), 2, gs.GS_F32)
+    assert pr(y, ap((4, 6), 2, gs.GS_F32), y) == gs.GS_ERR_SHAPE
+    assert pr(y, ap((4, 5), 2, gs.GS_BF16), y) == gs.GS_ERR_DTYPE
+    assert pr(ap((4, 5), 1, gs.GS_F32), ap((4, 5), 1, gs.GS_F32), y) == gs.GS_ERR_RANK   # compute dims would be folded
+
+
+def test_windows_reduce_validation():
+    L = gs.lib()
+    call = lambda a, win, st, out, op=gs.GS_MAX: L.glenside_windows_reduce(
+        ctypes.byref(a), win, st, None, None, op, ctypes.c_float(1.0), ctypes.byref(out), None)
+    x = ap((2, 3, 8, 8), 2)
+    assert call(x, i64(2, 2), i64(2, 2), ap((2, 3, 4, 3), 4)) == gs.GS_ERR_SHAPE
+    assert call(x, i64(9, 2), i64(2, 2), ap((2, 3, 4, 4), 4)) == gs.GS_ERR_SHAPE
+    assert call(x, i64(2, 2), i64(2, 2), ap((2, 3, 4, 4), 4, gs.GS_I32)) == gs.GS_ERR_DTYPE

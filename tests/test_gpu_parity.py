@@ -1,0 +1,279 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
+
+Integer results must be bit-exact; bf16-in / fp32-accumulate results must be within 1e-2 maximum
+relative error (floor 1e-3 * max|ref| on the denominator).  Sizes span several tiles and ragged
+tails of the kernels' 32/64/128-wide tiles.
+"""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import access_pattern as ap
+from oracle import brute
+from oracle import programs as pg
+from paper_2105_09377_amd import binding as gs
+from paper_2105_09377_amd import synth
+from helpers import assert_parity, to_oracle
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def gen(dtype, shape, stream, scale=1.0):
+    if dtype == "i8":
+        return synth.uniform_int8(shape, -127, 127, stream)
+    if dtype == "i32":
+        return synth.uniform_int32(shape, -100000, 100000, stream)
+    if dtype == "bf16":
+        return synth.normal_bf16(shape, scale, stream)
+    return synth.normal_f32(shape, scale, stream)
+
+
+def oracle_windows(x, n_access, window, stride, pad_lo, pad_hi, fill):
+    node = ap.tensor(to_oracle(x))
+    nc = x.dim() - n_access
+    for d in range(nc):
+        lo = pad_lo[d] if pad_lo else 0
+        hi = pad_hi[d] if pad_hi else 0
+        if lo or hi:
+            node = ap.pad(node, n_access + d, lo, hi, fill)
+    return ap.windows(ap.access(node, n_access), window, stride)
+
+
+LOWEST = {"i8": -128, "i32": -2 ** 31, "bf16": -np.inf, "f32": -np.inf}
+
+# ---------------------------------------------------------------------------------------------
+# windows
+# ---------------------------------------------------------------------------------------------
+
+WINDOW_CASES = [
+    # dtype, shape, n_access, window, stride, pad_lo, pad_hi, pad_mode
+    ("f32", (5, 37), 1, (4,), (3,), None, None, gs.GS_PAD_ZERO),
+    ("bf16", (2, 3, 9, 11), 2, (3, 2), (2, 3), (1, 0), (1, 1), gs.GS_PAD_LOWEST),
+    ("i8", (1, 3, 8, 8), 1, (3, 3, 3), (1, 1, 1), None, None, gs.GS_PAD_ZERO),
+    ("i8", (2, 5, 13, 10), 1, (5, 3, 3), (1, 2, 2), (0, 1, 1), (0, 1, 1), gs.GS_PAD_ZERO),
+    ("bf16", (3, 16, 20, 20), 1, (16, 3, 3), (1, 1, 1), (0, 1, 1), (0, 1, 1), gs.GS_PAD_ZERO),
+    ("i32", (2, 2, 6, 7), 2, (2, 2), (2, 2), None, None, gs.GS_PAD_LOWEST),
+    ("bf16", (2, 3, 15, 15), 1, (3, 7, 7), (1, 2, 2), (0, 3, 3), (0, 3, 3), gs.GS_PAD_ZERO),
+]
+
+
+@pytest.mark.parametrize("case", WINDOW_CASES)
+def test_access_windows(case):
+    dtype, shape, na, window, stride, lo, hi, mode = case
+    x = gen(dtype, shape, 1000 + len(shape) + shape[-1])
+    got = gs.access_windows(x.to(DEV), na, window, stride, lo, hi, mode)
+    fill = LOWEST[dtype] if mode == gs.GS_PAD_LOWEST else 0
+    want = oracle_windows(x, na, window, stride, lo, hi, fill).materialize()
+    got_np = to_oracle(got)
+    assert got_np.shape == want.shape
+    np.testing.assert_array_equal(got_np, want)          # a gather is exact in every dtype
+
+
+def test_access_windows_is_the_im2col_matrix():
+    """flatten(windows ...) of Fig. 5 is the same memory as the windows result."""
+    x = gen("i8", (2, 4, 9, 9), 1100)
+    got = gs.access_windows(x.to(DEV), 1, (4, 3, 3), (1, 2, 2), (0, 1, 1), (0, 1, 1))
+    want = pg.im2col_matrix(ap.tensor(to_oracle(x)), (4, 3, 3), (2, 2), (1, 1)).materialize()
+    np.testing.assert_array_equal(to_oracle(got).reshape(want.shape), want)
+
+
+# ---------------------------------------------------------------------------------------------
+# compute dotProd (cartProd a0 a1)
+# ---------------------------------------------------------------------------------------------
+
+DOT_CASES = [
+    # dtype, a0 shape, n0, a1 shape, n1, out dtype, relu
+    ("i8", (36, 27), 1, (4, 27), 1, torch.int32, False),          # the tiny conv's im2col product
+    ("i8", (300, 328), 1, (200, 328), 1, torch.int32, False),     # ragged tiles, K not a slab multiple
+    ("i8", (130, 1000), 1, (70, 1000), 1, torch.int32, True),
+    ("bf16", (256, 784), 1, (512, 784), 1, torch.float32, True),  # MLP layer 1
+    ("bf16", (256, 512), 1, (10, 512), 1, torch.float32, False),  # MLP layer 3
+    ("bf16", (100, 147), 1, (64, 147), 1, torch.bfloat16, False), # K = 147: unaligned rows
+    ("bf16", (2, 3, 4, 5), 2, (7, 4, 5), 1, torch.float32, False),  # multi-dim access and compute shapes
+    ("bf16", (513, 64), 1, (129, 64), 1, torch.bfloat16, True),
+    ("i8", (1, 5), 1, (1, 5), 1, torch.int32, False),
+]
+
+
+@pytest.mark.parametrize("case", DOT_CASES)
+def test_cartesian_dot(case):
+    dtype, s0, n0, s1, n1, odt, relu = case
+    k = int(np.prod(s0[n0:]))
+    a0 = gen(dtype, s0, 1200 + s0[0], 1.0)
+    a1 = gen(dtype, s1, 1300 + s1[0], 1.0 / np.sqrt(k) if dtype == "bf16" else 1.0)
+    got = gs.cartesian_dot(a0.to(DEV), a1.to(DEV), n0, n1, odt, gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE)
+    prog = pg.cartesian_dot(ap.access(ap.tensor(to_oracle(a0)), n0), ap.access(ap.tensor(to_oracle(a1)), n1))
+    if relu:
+        prog = ap.compute(ap.relu, prog)
+    assert tuple(got.shape) == prog.access_shape
+    assert_parity(got, prog.materialize(), what=str(case))
+
+
+def test_cartesian_dot_extreme_int8_values():
+    """-128 * -128 * K stays exact in int32."""
+    a0 = torch.full((40, 512), -128, dtype=torch.int8)
+    a1 = torch.full((33, 512), -128, dtype=torch.int8)
+    got = gs.cartesian_dot(a0.to(DEV), a1.to(DEV))
+    assert (got.cpu() == 128 * 128 * 512).all()
+
+
+def test_cartesian_dot_empty():
+    a0 = torch.zeros((0, 16), dtype=torch.bfloat16, device=DEV)
+    a1 = torch.zeros((8, 16), dtype=torch.bfloat16, device=DEV)
+    assert gs.cartesian_dot(a0, a1).shape == (0, 8)
+
+
+# ---------------------------------------------------------------------------------------------
+# conv2d, both forms
+# ---------------------------------------------------------------------------------------------
+
+CONV_CASES = [
+    # dtype, N, C, H, W, O, Kh, Kw, stride, pad, out dtype
+    ("i8", 1, 3, 8, 8, 4, 3, 3, (1, 1), (0, 0), torch.int32),          # tiny configuration
+    ("i8", 3, 40, 13, 13, 70, 3, 3, (1, 1), (1, 1), torch.int32),       # odd W, ragged C / O / M tails
+    ("i8", 2, 64, 20, 18, 33, 3, 3, (2, 2), (1, 1), torch.int32),
+    ("bf16", 2, 16, 20, 20, 24, 3, 3, (1, 1), (1, 1), torch.float32),
+    ("bf16", 5, 32, 7, 7, 130, 3, 3, (1, 1), (1, 1), torch.bfloat16),   # 49-position planes: tiles span images
+    ("bf16", 3, 24, 14, 14, 48, 1, 1, (2, 2), (0, 0), torch.float32),   # 1x1 stride-2 projection
+    ("bf16", 2, 3, 30, 30, 16, 7, 7, (2, 2), (3, 3), torch.bfloat16),   # 7x7/2 pad 3, C = 3
+    ("bf16", 1, 48, 9, 11, 20, 3, 2, (1, 2), (0, 1), torch.float32),    # non-square everything
+    ("bf16", 2, 128, 12, 12, 64, 3, 3, (1, 1), (1, 1), torch.float32),  # several channel chunks
+]
+
+
+def conv_inputs(case):
+    dtype, n, c, h, w, o, kh, kw, stride, pad, odt = case
+    x = gen(dtype, (n, c, h, w), 1400 + c + h)
+    wt = gen(dtype, (o, c, kh, kw), 1500 + o, 1.0 / np.sqrt(c * kh * kw) if dtype == "bf16" else 1.0)
+    return x, wt
+
+
+def conv_oracle(x, wt, stride, pad):
+    xo, wo = to_oracle(x), to_oracle(wt)
+    macs = x.shape[0] * wt.shape[0] * x.shape[2] * x.shape[3] * wt[0].numel()
+    if macs <= 4_000_000:
+        return pg.conv2d(ap.tensor(xo), ap.tensor(wo), stride, pad).materialize()
+    return brute.conv2d(xo, wo, stride, pad)
+
+
+@pytest.mark.parametrize("form", ["direct", "im2col"])
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv2d(case, form):
+    x, wt = conv_inputs(case)
+    stride, pad, odt = case[8], case[9], case[10]
+    fn = gs.conv2d_direct if form == "direct" else gs.conv2d_im2col
+    got = fn(x.to(DEV), wt.to(DEV), stride, pad, out_dtype=odt)
+    assert_parity(got, conv_oracle(x, wt, stride, pad), what=f"{form} {case}")
+
+
+def test_conv2d_direct_equals_im2col_bitwise_int8():
+    """The rewrite of Sec. 5.3 preserves the result: both forms agree bit for bit on integers."""
+    case = ("i8", 4, 32, 17, 19, 40, 3, 3, (1, 1), (1, 1), torch.int32)
+    x, wt = conv_inputs(case)
+    a = gs.conv2d_direct(x.to(DEV), wt.to(DEV), (1, 1), (1, 1))
+    b = gs.conv2d_im2col(x.to(DEV), wt.to(DEV), (1, 1), (1, 1))
+    assert torch.equal(a, b)
+    assert_parity(a, conv_oracle(x, wt, (1, 1), (1, 1)))
+
+
+@pytest.mark.parametrize("form", ["direct", "im2col"])
+@pytest.mark.parametrize("dtype,odt", [("i8", torch.int32), ("bf16", torch.bfloat16), ("bf16", torch.float32)])
+def test_conv2d_residual_relu(form, dtype, odt):
+    case = (dtype, 2, 32, 10, 10, 40, 3, 3, (1, 1), (1, 1), odt)
+    x, wt = conv_inputs(case)
+    if odt == torch.int32:
+        res = synth.uniform_int32((2, 40, 10, 10), -50000, 50000, 1601)
+    elif odt == torch.bfloat16:
+        res = synth.normal_bf16((2, 40, 10, 10), 1.0, 1602)
+    else:
+        res = synth.normal_f32((2, 40, 10, 10), 1.0, 1603)
+    fn = gs.conv2d_direct if form == "direct" else gs.conv2d_im2col
+    got = fn(x.to(DEV), wt.to(DEV), (1, 1), (1, 1), residual=res.to(DEV), act=gs.GS_ACT_RELU, out_dtype=odt)
+    conv = pg.conv2d(ap.tensor(to_oracle(x)), ap.tensor(to_oracle(wt)), (1, 1), (1, 1))
+    prog = ap.compute(ap.relu, pg.add(conv, ap.access(ap.tensor(to_oracle(res)), 4)))
+    assert_parity(got, prog.materialize(), what=f"{form} {dtype} residual+relu")
+
+
+def test_conv2d_minus_128_and_empty_batch():
+    x = torch.full((1, 32, 6, 6), -128, dtype=torch.int8)
+    w = torch.full((8, 32, 3, 3), -128, dtype=torch.int8)
+    got = gs.conv2d_direct(x.to(DEV), w.to(DEV), (1, 1), (1, 1))
+    assert_parity(got, conv_oracle(x, w, (1, 1), (1, 1)))
+    empty = torch.zeros((0, 32, 6, 6), dtype=torch.int8, device=DEV)
+    assert gs.conv2d_direct(empty, w.to(DEV), (1, 1), (1, 1)).shape == (0, 8, 6, 6)
+    assert gs.conv2d_im2col(empty, w.to(DEV), (1, 1), (1, 1)).shape == (0, 8, 6, 6)
+
+
+# ---------------------------------------------------------------------------------------------
+# reduce, pooling, pair
+# ---------------------------------------------------------------------------------------------
+
+REDUCE_CASES = [
+    ("i8", (7, 13), 1), ("i8", (3, 5, 4), 1), ("i32", (10, 49), 1), ("bf16", (6, 5, 7, 7), 2),
+    ("f32", (33, 100), 1), ("bf16", (3, 5000), 1), ("f32", (1000, 1), 1), ("i32", (2, 9000), 1),
+    ("bf16", (513, 4), 1), ("f32", (5,), 0),
+]
+
+
+@pytest.mark.parametrize("op", [gs.GS_SUM, gs.GS_MAX])
+@pytest.mark.parametrize("case", REDUCE_CASES)
+def test_reduce(case, op):
+    dtype, shape, na = case
+    x = gen(dtype, shape, 1700 + len(shape) + shape[0])
+    got = gs.reduce(x.to(DEV), na, op)
+    oper = ap.reduceSum if op == gs.GS_SUM else ap.reduceMax
+    want = ap.compute(oper, ap.access(ap.tensor(to_oracle(x)), na)).materialize()
+    if op == gs.GS_MAX:
+        np.testing.assert_array_equal(to_oracle(got), want)      # max is exact in every dtype
+    else:
+        assert_parity(got, want, float_tol=1e-2 if dtype == "bf16" else 1e-4, what=str(case))
+
+
+def test_reduce_scaled_mean_is_global_average_pool():
+    x = gen("bf16", (4, 24, 7, 7), 1801)
+    got = gs.reduce(x.to(DEV), 2, gs.GS_SUM, scale=1.0 / 49.0)
+    prog = ap.compute(ap.scale(1.0 / 49.0), ap.compute(ap.reduceSum, ap.access(ap.tensor(to_oracle(x)), 2)))
+    assert_parity(got, prog.materialize())
+
+
+POOL_CASES = [
+    ("bf16", (2, 5, 14, 14), (2, 2), (2, 2), None),
+    ("bf16", (2, 3, 17, 16), (3, 3), (2, 2), (1, 1)),
+    ("i8", (1, 4, 9, 12), (3, 2), (1, 2), (1, 0)),
+    ("f32", (2, 2, 8, 8), (8, 8), (1, 1), None),
+    ("i32", (3, 3, 10, 10), (2, 2), (2, 2), None),
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES)
+def test_max_pool_fused_and_unfused(case):
+    dtype, shape, window, stride, pad = case
+    x = gen(dtype, shape, 1900 + shape[-1])
+    xd = x.to(DEV)
+    fused = gs.windows_reduce(xd, 2, window, stride, pad, pad, gs.GS_MAX)
+    win = gs.access_windows(xd, 2, window, stride, pad, pad, gs.GS_PAD_LOWEST)
+    unfused = gs.reduce(win, 4, gs.GS_MAX)
+    want = pg.max_pool2d(ap.tensor(to_oracle(x)), window, stride, pad or (0, 0), LOWEST[dtype]).materialize()
+    np.testing.assert_array_equal(to_oracle(fused), want)
+    assert torch.equal(fused, unfused)
+
+
+def test_sum_pool_and_1d_windows_reduce():
+    x = gen("f32", (3, 40), 1950)
+    got = gs.windows_reduce(x.to(DEV), 1, (5,), (3,), (2,), (2,), gs.GS_SUM, scale=0.2)
+    node = ap.windows(ap.access(ap.pad(ap.tensor(to_oracle(x)), 1, 2, 2, 0.0), 1), (5,), (3,))
+    want = ap.compute(ap.scale(0.2), ap.compute(ap.reduceSum, node)).materialize()
+    assert_parity(got, want, float_tol=1e-5)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "bf16", "f32"])
+@pytest.mark.parametrize("op", [gs.GS_SUM, gs.GS_MAX])
+def test_pair_reduce(dtype, op):
+    a, b = gen(dtype, (3, 5, 7, 11), 2001), gen(dtype, (3, 5, 7, 11), 2002)
+    got = gs.pair_reduce(a.to(DEV), b.to(DEV), op, gs.GS_ACT_RELU)
+    oper = ap.reduceSum if op == gs.GS_SUM else ap.reduceMax
+    pr = ap.pair(ap.access(ap.tensor(to_oracle(a)), 4), ap.access(ap.tensor(to_oracle(b)), 4))
+    want = ap.compute(ap.relu, ap.compute(oper, pr)).materialize()
+    assert_parity(got, want, float_tol=1e-2 if dtype == "bf16" else 1e-6)
