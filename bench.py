@@ -1,0 +1,158 @@
+"""Benchmark of the access-pattern hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18|conv3x3]
+
+A step is one pass of the workload's whole call sequence over one batch of synthetic input that
+is already resident in HBM.  Steps are captured once into HIP graphs (one per rotating buffer
+set, so that consecutive steps do not find their inputs in cache) and replayed; the timed region
+is exactly K steps between two device synchronisations.  Prints one JSON line.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import torch  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+ROTATE_BYTES = 512 << 20      # rotate over enough buffer sets to exceed the last-level cache
+
+
+def _graph_of(fn, stream):
+    """Capture fn() (already warmed up) into a HIP graph on `stream`."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        fn()
+    return g
+
+
+def _time_region(launchers, steps, stream):
+    """Run `steps` launches (launcher i % len) and return (wall seconds, event milliseconds)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        start.record(stream)
+        for i in range(steps):
+            launchers[i % len(launchers)]()
+        stop.record(stream)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0, start.elapsed_time(stop)
+
+
+class Conv3x3:
+    """ResNet-style 3x3 convolution: N=32, C=64, 56x56 -> 64 channels, stride 1, pad 1, bf16."""
+
+    name = "resnet-style 3x3 conv N=32 C=64 H=W=56 O=64 s1 p1, bf16 in/out, fp32 accumulate"
+    dominant = "conv_direct_kernel"
+
+    def __init__(self, dev):
+        from paper_2105_09377_amd import binding as gs, synth
+        self.gs = gs
+        cfg = synth.resnet_conv3x3("bf16", 32)
+        self.cfg = cfg
+        x, w = cfg["x"], cfg["w"]
+        self.flops = 2.0 * 32 * 56 * 56 * 64 * 64 * 9
+        set_bytes = 2 * x.numel() * 2
+        self.nsets = max(2, min(48, -(-ROTATE_BYTES // set_bytes)))
+        self.w = w.to(dev)
+        self.xs = [x.to(dev).clone() for _ in range(self.nsets)]
+        self.outs = [torch.empty((32, 64, 56, 56), dtype=torch.bfloat16, device=dev) for _ in range(self.nsets)]
+        self.ws = torch.empty(gs.conv2d_workspace(self.xs[0], self.w, (1, 1), (1, 1)), dtype=torch.uint8, device=dev)
+        self.packed = gs.conv2d_pack_weights(self.w)
+
+    def step(self, i):
+        """The public entry point as a user calls it: weight packing + convolution."""
+        self.gs.conv2d_direct(self.xs[i], self.w, (1, 1), (1, 1), out=self.outs[i], workspace=self.ws)
+
+    def dominant_launch(self, i):
+        """The convolution kernel alone (weights packed beforehand)."""
+        self.gs.conv2d_direct_packed(self.xs[i], self.w, self.packed, (1, 1), (1, 1), out=self.outs[i])
+
+    dominant_flops = property(lambda self: self.flops)
+
+    def cpu_baseline(self):
+        import numpy as np
+        from oracle import brute, numerics
+        n = 32
+        x = self.cfg["x"][:n].contiguous()
+        xo = numerics.bf16_bits_to_f64(x.view(torch.int16).numpy().view(np.uint16))
+        wo = numerics.bf16_bits_to_f64(self.cfg["w"].view(torch.int16).numpy().view(np.uint16))
+        brute.conv2d(xo[:1], wo, (1, 1), (1, 1))
+        t0 = time.perf_counter()
+        brute.conv2d(xo, wo, (1, 1), (1, 1))
+        dt = time.perf_counter() - t0
+        return {"value": self.flops * n / 32 / dt / 1e12, "unit": "TFLOP/s", "cores": brute.num_threads(),
+                "kind": "oracle", "sample": f"brute-force C loops (fp64, OpenMP) on all {n} images of the workload, {dt:.2f} s"}
+
+
+WORKLOADS = {"conv3x3": Conv3x3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="conv3x3", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = WORKLOADS[args.workload](dev)
+    stream = torch.cuda.Stream(device=dev)
+
+    with torch.cuda.stream(stream):
+        for i in range(wl.nsets):           # first calls set kernel attributes: not capturable
+            wl.step(i)
+            wl.dominant_launch(i)
+    torch.cuda.synchronize()
+    step_graphs = [_graph_of(lambda i=i: wl.step(i), stream) for i in range(wl.nsets)]
+    dom_graphs = [_graph_of(lambda i=i: wl.dominant_launch(i), stream) for i in range(wl.nsets)]
+    step_launch = [g.replay for g in step_graphs]
+    dom_launch = [g.replay for g in dom_graphs]
+
+    _time_region(step_launch, args.warmup, stream)
+    wall, ev_ms = _time_region(step_launch, args.steps, stream)
+    ms_per_step = wall * 1e3 / args.steps
+
+    _time_region(dom_launch, args.warmup, stream)
+    _, dom_ms = _time_region(dom_launch, args.steps, stream)
+    dom_s = dom_ms * 1e-3 / args.steps
+    achieved = wl.dominant_flops / dom_s / 1e12
+
+    out = {
+        "metric": "conv2d/matmul TFLOP/s + % MFMA peak; im2col/reduce GB/s + % HBM peak",
+        "value": wl.flops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "buffer_sets": wl.nsets, "launch": "hip graph replay"},
+        "event_ms_per_step": ev_ms / args.steps,
+        "roofline": {"bound": "mfma", "kernel": wl.dominant, "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "us_per_launch": dom_s * 1e6, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = wl.cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

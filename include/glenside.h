@@ -108,6 +108,20 @@ int glenside_conv2d_direct(const gs_ap* activations, const gs_ap* weights, const
 int glenside_conv2d_im2col(const gs_ap* activations, const gs_ap* weights, const int64_t stride[2],
                            const int64_t pad[2], const gs_ap* residual, int act, gs_ap* out,
                            void* workspace, size_t workspace_bytes, void* stream);
+/* The two halves of glenside_conv2d_direct, for callers whose weights are constants.
+ *   _pack_weights  : writes the weight access pattern ((O),(C,Kh,Kw)) into `packed` in the order
+ *                    the contraction reads it, (O, Kh, Kw, C) with C padded to a 32-byte step --
+ *                    the weight-side layout change that the systolic-array rewrite (Sec. 5.2) makes
+ *                    explicit with (transpose ?a1 ...).  Needs glenside_conv2d_direct_workspace bytes.
+ *   _direct_packed : the convolution proper, reading weights only from `packed`; `weights` gives
+ *                    shape and dtype, its data pointer is not read.
+ * glenside_conv2d_direct(x, w, ..., ws) == _pack_weights(w, ws) then _direct_packed(x, w, ..., ws). */
+int glenside_conv2d_pack_weights(const gs_ap* weights, void* packed, size_t packed_bytes,
+                                 void* stream);
+int glenside_conv2d_direct_packed(const gs_ap* activations, const gs_ap* weights,
+                                  const int64_t stride[2], const int64_t pad[2],
+                                  const gs_ap* residual, int act, gs_ap* out, const void* packed,
+                                  size_t packed_bytes, void* stream);
 /* Workspace bytes the two forms need; 0 if the arguments are invalid.  Host only. */
 size_t glenside_conv2d_direct_workspace(const gs_ap* activations, const gs_ap* weights,
                                         const int64_t stride[2], const int64_t pad[2]);

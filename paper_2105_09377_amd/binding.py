@@ -31,7 +31,8 @@ EXPORTS = (
     "glenside_status_string", "glenside_windows_out_shape", "glenside_access_windows",
     "glenside_cartesian_dot", "glenside_conv2d_direct", "glenside_conv2d_im2col",
     "glenside_conv2d_direct_workspace", "glenside_conv2d_im2col_workspace", "glenside_reduce",
-    "glenside_windows_reduce", "glenside_pair_reduce",
+    "glenside_windows_reduce", "glenside_pair_reduce", "glenside_conv2d_pack_weights",
+    "glenside_conv2d_direct_packed",
 )
 
 
@@ -69,6 +70,8 @@ def lib() -> ctypes.CDLL:
         for f in (L.glenside_conv2d_direct_workspace, L.glenside_conv2d_im2col_workspace):
             f.restype = ctypes.c_size_t
             f.argtypes = [ap_p, ap_p, i64_p, i64_p]
+        L.glenside_conv2d_pack_weights.argtypes = [ap_p, vp, ctypes.c_size_t, vp]
+        L.glenside_conv2d_direct_packed.argtypes = conv
         L.glenside_reduce.argtypes = [ap_p, ctypes.c_int, ctypes.c_float, ap_p, vp]
         L.glenside_windows_reduce.argtypes = [ap_p, i64_p, i64_p, i64_p, i64_p, ctypes.c_int,
                                               ctypes.c_float, ap_p, vp]
@@ -190,6 +193,28 @@ def conv2d_direct(x, w, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NON
     """Fig. 2a with the windows formed on chip; x (N,C,H,W), w (O,C,Kh,Kw) -> (N,O,H',W')."""
     return _conv("glenside_conv2d_direct", "glenside_conv2d_direct_workspace", x, w, stride, pad,
                  residual, act, out_dtype, out, workspace)
+
+
+def conv2d_pack_weights(w: torch.Tensor, packed: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Weights (O,C,Kh,Kw) -> the packed form `conv2d_direct_packed` reads (a uint8 buffer)."""
+    L = lib()
+    wa = make_ap(w, 1)
+    if packed is None:
+        fake_x = gs_ap()
+        fake_x.dtype, fake_x.rank, fake_x.n_access = wa.dtype, 4, 1
+        fake_x.shape[0], fake_x.shape[1], fake_x.shape[2], fake_x.shape[3] = 1, w.shape[1], w.shape[2], w.shape[3]
+        need = L.glenside_conv2d_direct_workspace(ctypes.byref(fake_x), ctypes.byref(wa), _i64((1, 1)), _i64((0, 0)))
+        packed = torch.empty(max(int(need), 16), dtype=torch.uint8, device=w.device)
+    _check(L.glenside_conv2d_pack_weights(ctypes.byref(wa), packed.data_ptr(), packed.numel(), _stream(w)),
+           "conv2d_pack_weights")
+    return packed
+
+
+def conv2d_direct_packed(x, w, packed, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NONE,
+                         out_dtype=None, out=None) -> torch.Tensor:
+    """Fig. 2a reading weights from `conv2d_pack_weights(w)`; `w` supplies shape and dtype only."""
+    return _conv("glenside_conv2d_direct_packed", "glenside_conv2d_direct_workspace", x, w, stride, pad,
+                 residual, act, out_dtype, out, packed)
 
 
 def conv2d_im2col(x, w, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NONE, out_dtype=None,

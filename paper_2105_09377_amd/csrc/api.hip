@@ -268,24 +268,40 @@ size_t glenside_conv2d_im2col_workspace(const gs_ap* act, const gs_ap* w, const 
   return size_t(round_up(M * ld * esz, 256) + round_up(int64_t(cs.O) * ld * esz, 256) + 256);
 }
 
-int glenside_conv2d_direct(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
-                           const int64_t pad[2], const gs_ap* residual, int actfn, gs_ap* out,
-                           void* workspace, size_t workspace_bytes, void* stream) {
+int glenside_conv2d_pack_weights(const gs_ap* w, void* packed, size_t packed_bytes, void* stream) {
+  int st = check_ap(w, true);
+  if (st) return st;
+  if (w->rank != 4 || w->n_access != 1) return GS_ERR_RANK;
+  if (w->dtype != GS_I8 && w->dtype != GS_BF16) return GS_ERR_DTYPE;
+  for (int i = 0; i < 4; ++i)
+    if (w->shape[i] > INT_MAX / 4) return GS_ERR_UNSUPPORTED;
+  if (w->shape[1] < 1 || w->shape[2] < 1 || w->shape[3] < 1) return GS_ERR_SHAPE;
+  const int O = int(w->shape[0]), C = int(w->shape[1]), Kh = int(w->shape[2]), Kw = int(w->shape[3]);
+  const size_t need = size_t(round_up(int64_t(conv_weight_workspace(w->dtype, O, C, Kh, Kw)), 256)) + 256;
+  if (!packed || packed_bytes < need || reinterpret_cast<uintptr_t>(packed) % 16)
+    return GS_ERR_WORKSPACE;
+  return launch_status(launch_conv_repack(w->data, packed, w->dtype, O, C, Kh, Kw,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int glenside_conv2d_direct_packed(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                                  const int64_t pad[2], const gs_ap* residual, int actfn,
+                                  gs_ap* out, const void* packed, size_t packed_bytes,
+                                  void* stream) {
   ConvShape cs;
   int st = conv_shape(act, w, stride, pad, &cs);
   if (st) return st;
-  st = conv_check_io(act, w, residual, actfn, out, cs);
+  gs_ap wshape = *w;            // the packed form carries the data; only the shape is used
+  wshape.data = const_cast<void*>(packed);
+  st = conv_check_io(act, &wshape, residual, actfn, out, cs);
   if (st) return st;
   const size_t need = glenside_conv2d_direct_workspace(act, w, stride, pad);
-  if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16)
+  if (!packed || packed_bytes < need || reinterpret_cast<uintptr_t>(packed) % 16)
     return GS_ERR_WORKSPACE;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = launch_conv_repack(w->data, workspace, act->dtype, cs.O, cs.C, cs.Kh, cs.Kw, s);
-  if (e != hipSuccess) return launch_status(e);
   ConvArgs a;
   memset(&a, 0, sizeof(a));
   a.act = act->data;
-  a.wr = workspace;
+  a.wr = packed;
   a.out = out->data;
   a.residual = residual ? residual->data : nullptr;
   a.in_dtype = act->dtype;
@@ -294,7 +310,25 @@ int glenside_conv2d_direct(const gs_ap* act, const gs_ap* w, const int64_t strid
   a.Sh = cs.Sh; a.Sw = cs.Sw; a.Ph = cs.Ph; a.Pw = cs.Pw; a.Ho = cs.Ho; a.Wo = cs.Wo;
   a.Cpad = int(conv_weight_workspace(act->dtype, 1, cs.C, 1, 1) / dtype_size(act->dtype));
   a.relu = actfn == GS_ACT_RELU;
-  return launch_status(launch_conv(a, s));
+  return launch_status(launch_conv(a, static_cast<hipStream_t>(stream)));
+}
+
+int glenside_conv2d_direct(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                           const int64_t pad[2], const gs_ap* residual, int actfn, gs_ap* out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  // Validate everything first so that a bad call launches nothing, then run the two halves.
+  ConvShape cs;
+  int st = conv_shape(act, w, stride, pad, &cs);
+  if (st) return st;
+  st = conv_check_io(act, w, residual, actfn, out, cs);
+  if (st) return st;
+  const size_t need = glenside_conv2d_direct_workspace(act, w, stride, pad);
+  if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 16)
+    return GS_ERR_WORKSPACE;
+  st = glenside_conv2d_pack_weights(w, workspace, workspace_bytes, stream);
+  if (st) return st;
+  return glenside_conv2d_direct_packed(act, w, stride, pad, residual, actfn, out, workspace,
+                                       workspace_bytes, stream);
 }
 
 int glenside_conv2d_im2col(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
