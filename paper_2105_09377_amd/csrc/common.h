@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "../../include/glenside.h"
 
 namespace gs {
@@ -14,6 +17,33 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kWave = 64;
+
+// Compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>).  Unlike `#pragma unroll`, which
+// the optimiser may decline for large bodies, this always yields constant indices, so register
+// arrays indexed by the loop variable never fall back to scratch memory.
+template <int N, typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl<N>(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+// Workgroup barrier that orders LDS traffic only.  `__syncthreads()` also waits for every global
+// load of the wave, which would drain software prefetches that are meant to stay in flight
+// across the barrier; this one waits for LDS operations alone.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+// Wait until at most N of this wave's vector-memory loads (which complete in order) are still
+// outstanding.  N above the counter's range waits for more than necessary, never less.
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N < 63 ? N : 63) : "memory");
+}
 
 __host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 __host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
@@ -59,8 +89,8 @@ struct I8Traits {
 // Epilogue shared by the contractions: optional residual, optional ReLU, store in the output
 // type.  `addr` is an element offset.
 template <typename AccT>
-__device__ inline void store_result(void* out, const void* residual, int out_dtype, int64_t addr,
-                                    AccT v, int relu) {
+__device__ __forceinline__ void store_result(void* out, const void* residual, int out_dtype,
+                                             int64_t addr, AccT v, int relu) {
   if constexpr (sizeof(AccT) == 4 && __is_same(AccT, int32_t)) {
     int32_t r = v;
     if (residual) r += static_cast<const int32_t*>(residual)[addr];

@@ -1,0 +1,72 @@
+// One translation unit per (element type, tile shape) of the pipelined convolution kernel, so
+// that the many template instances compile in parallel.  Built several times with different
+// -DGS_CONV3_TRAITS / -DGS_CONV3_TILE / -DGS_CONV3_NAME (see build.py).
+#include "conv_kernels.h"
+
+namespace gs {
+
+// Pipelined kernel launcher: returns hipErrorInvalidValue when this shape does not fit it.
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int D>
+static hipError_t launch_conv3_cfg(const ConvArgs& a, ConvGeom g, hipStream_t s) {
+  constexpr int MAXI = VW * TR::kEsz >= 16 ? 1 : (VW * TR::kEsz >= 8 ? 2 : 3);   // bounds the register ring
+  g.max_rows = conv_max_rows(a, g.M, g.HWo, TP);
+  if (g.max_rows < 0) return hipErrorInvalidValue;
+  const int64_t items = int64_t(g.max_rows) * (a.W / VW) * 2;
+  if (items > 256 * MAXI) return hipErrorInvalidValue;
+  const size_t lds_bytes = 1024 + 3 * size_t(a.Kh * a.Kw) * TO * 32 + 2 * size_t(g.max_rows) * g.PW * 48;
+  if (lds_bytes > size_t(kLdsLimit)) return hipErrorInvalidValue;
+  auto kern = conv_direct3_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, D>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int64_t tiles = ceil_div(g.M, TP) * ceil_div(a.O, TO);
+  const int64_t per_cu = lds_bytes <= size_t(kLdsLimit) / 2 ? 2 : 1;
+  const int64_t grid = tiles < per_cu * conv_num_cus() ? tiles : per_cu * conv_num_cus();
+  hipLaunchKernelGGL(kern, dim3(unsigned(grid)), dim3(256), lds_bytes, s, a, g);
+  return hipGetLastError();
+}
+
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW>
+static hipError_t launch_conv3_depth(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
+  const int nchunk = a.Cpad / (32 / TR::kEsz);
+  if (nchunk < 2) return hipErrorInvalidValue;
+  if (nchunk % 4 == 0) return launch_conv3_cfg<TR, TO, TP, WO, WP, VW, KH, KW, 4>(a, g, s);
+  if (nchunk % 2 == 0) return launch_conv3_cfg<TR, TO, TP, WO, WP, VW, KH, KW, 2>(a, g, s);
+  return hipErrorInvalidValue;   // odd chunk counts take the general kernel
+}
+
+template <typename TR, int TO, int TP, int WO, int WP, int VW>
+static hipError_t launch_conv3_taps(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
+  if (a.Kh == 3 && a.Kw == 3) return launch_conv3_depth<TR, TO, TP, WO, WP, VW, 3, 3>(a, g, s);
+  return launch_conv3_depth<TR, TO, TP, WO, WP, VW, 0, 0>(a, g, s);
+}
+
+template <typename TR, int TO, int TP, int WO, int WP>
+static hipError_t launch_conv3_vw(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
+  constexpr int ESZ = TR::kEsz;
+  // Widest pixel vector whose loads stay aligned: W (hence every row start) a multiple of it.
+  if (a.W % 8 == 0) return launch_conv3_taps<TR, TO, TP, WO, WP, 8>(a, g, s);
+  if (a.W % 4 == 0) return launch_conv3_taps<TR, TO, TP, WO, WP, 4>(a, g, s);
+  if (a.W % 2 == 0) return launch_conv3_taps<TR, TO, TP, WO, WP, 2>(a, g, s);
+  (void)ESZ;
+  return launch_conv3_taps<TR, TO, TP, WO, WP, 1>(a, g, s);
+}
+
+
+#if GS_CONV3_TILE == 0
+#define GS_TILE 128, 128, 2, 2
+#elif GS_CONV3_TILE == 1
+#define GS_TILE 64, 256, 1, 4
+#else
+#define GS_TILE 64, 128, 1, 4
+#endif
+
+hipError_t GS_CONV3_NAME(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
+  return launch_conv3_vw<GS_CONV3_TRAITS, GS_TILE>(a, g, s);
+}
+
+}  // namespace gs

@@ -5,68 +5,91 @@
 // with 16-byte loads and no transposition.  A workgroup of 4 waves owns a BM x BN output tile
 // (the concat-on-access-dimensions blocking of Sec. 5.4); the K loop walks 128-byte slabs (the
 // pair/reduceSum blocking on the compute dimension), double-buffered in LDS with the next slab's
-// global loads in flight while the current one feeds the MFMAs.  The kernel is written in bytes:
-// a slab row is 128 bytes = 64 bf16 or 128 int8, one MFMA eats 32 bytes of K per row.
+// global loads in flight while the current one feeds the MFMAs.  The kernels are written in
+// bytes: a slab row is 128 bytes = 64 bf16 or 128 int8, one MFMA eats 32 bytes of K per row.
+//
+// Two kernels:
+//   gemm_nt_dma_kernel     : aligned operands, K a whole number of slabs.  Slabs go global -> LDS
+//                            directly (global_load_lds, 16 bytes per lane, no register staging);
+//                            because such a load writes 64 x 16 contiguous bytes, rows cannot be
+//                            padded, so bank conflicts are avoided by an XOR swizzle of the
+//                            16-byte columns instead.
+//   gemm_nt_checked_kernel : everything else (ragged K, unaligned rows), register-staged, checked.
 //
 // Result element (i, j) is stored at (j / jp) * (I * jp) + i * jp + (j % jp): jp = J gives the
 // plain row-major ((I, J), ()) result; jp = H'*W' with j = flattened (n, h', w') and i = o gives
 // the (N, O, H', W') layout of the convolution listings, i.e. the reshape/squeeze/transpose tail
 // of Fig. 5 folded into the store.  Columns j sit on the lanes, so stores are coalesced along j.
+//
+// Workgroups are renumbered so that each of the 8 XCDs (which have private L2 caches and receive
+// consecutive workgroup ids round-robin) works on a compact block of the tile grid.
 #include "common.h"
+
+#include <stdlib.h>
 
 namespace gs {
 
-constexpr int kSlabBytes = 128;           // K bytes per slab row
+constexpr int kSlabBytes = 128;             // K bytes per slab row
 constexpr int kRowBytes = kSlabBytes + 16;  // LDS row stride: odd multiple of 16 B, conflict-free b128
+constexpr int kXcds = 8;
 
-// Load one 16-byte chunk of a slab row, zero beyond the row's K bytes.
+// Map the hardware workgroup id to a tile so that an XCD's workgroups cover a compact region:
+// XCD x gets the contiguous range of "logical" ids [x*n/8, (x+1)*n/8), and logical ids walk the
+// grid in column bands of `band` tile rows.
+__device__ inline void tile_of_block(int64_t bid, int64_t nblocks, int64_t tiles_i, int64_t tiles_j,
+                                     int64_t* ti, int64_t* tj) {
+  const int64_t per = nblocks / kXcds, rem = nblocks % kXcds;
+  const int64_t x = bid % kXcds, l = bid / kXcds;
+  // XCDs 0..rem-1 own (per + 1) ids.
+  const int64_t logical = x * per + (x < rem ? x : rem) + l;
+  constexpr int64_t band = 8;
+  const int64_t band_size = band * tiles_j;
+  const int64_t b = logical / band_size, r = logical % band_size;
+  const int64_t rows_here = (b * band + band <= tiles_i) ? band : tiles_i - b * band;
+  *ti = b * band + r % rows_here;
+  *tj = r / rows_here;
+}
+
+// General (checked) load of one 16-byte chunk: zero beyond the row's K bytes, byte loads when the
+// rows are not 16-byte aligned.  Used by the edge/unaligned kernel only.
 template <bool VEC>
-__device__ inline i32x4 load_chunk(const uint8_t* row_ptr, int64_t kb, int64_t Kb, bool row_ok) {
+__device__ inline i32x4 load_chunk_checked(const uint8_t* row_ptr, int64_t kb, int64_t Kb,
+                                           bool row_ok) {
   i32x4 v = {0, 0, 0, 0};
   if (!row_ok || kb >= Kb) return v;
   const int64_t nvalid = Kb - kb;
-  if constexpr (VEC) {
-    v = *reinterpret_cast<const i32x4*>(row_ptr + kb);
-    if (nvalid < 16) {
-      uint8_t* b = reinterpret_cast<uint8_t*>(&v);
-      for (int t = 0; t < 16; ++t)
-        if (t >= nvalid) b[t] = 0;
-    }
-  } else {
-    uint8_t* b = reinterpret_cast<uint8_t*>(&v);
-    for (int t = 0; t < 16; ++t)
-      if (t < nvalid) b[t] = row_ptr[kb + t];
-  }
+  if (VEC && nvalid >= 16) return *reinterpret_cast<const i32x4*>(row_ptr + kb);
+  uint32_t w[4] = {0, 0, 0, 0};
+  for (int t = 0; t < 16; ++t)
+    if (t < nvalid) w[t >> 2] |= uint32_t(row_ptr[kb + t]) << (8 * (t & 3));
+  v[0] = int32_t(w[0]); v[1] = int32_t(w[1]); v[2] = int32_t(w[2]); v[3] = int32_t(w[3]);
   return v;
 }
 
-template <typename TR, int BM, int BN, bool VEC>
-__global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  constexpr int WM = BM / 2, WN = BN / 2;     // wave tile
-  constexpr int MI = WM / 32, NJ = WN / 32;   // 32x32 MFMA blocks per wave
+// ---------------------------------------------------------------------------------------------
+// Checked kernel: any K, any alignment.  64x64 tile, 4 waves of 32x32, register-staged slabs.
+// ---------------------------------------------------------------------------------------------
+template <typename TR, bool VEC>
+__global__ void __launch_bounds__(256) gemm_nt_checked_kernel(GemmArgs a) {
+  constexpr int BM = 64, BN = 64;
   constexpr int XCH = BM * 8 / 256, YCH = BN * 8 / 256;   // 16-byte chunks per thread per slab
   constexpr int kXBytes = BM * kRowBytes, kYBytes = BN * kRowBytes;
   constexpr int kBuf = kXBytes + kYBytes;
+  __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kBuf];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int64_t tiles_j = ceil_div(a.J, BN);
   const int64_t i0 = (blockIdx.x / tiles_j) * BM, j0 = (blockIdx.x % tiles_j) * BN;
-
   const int64_t Kb = a.K * TR::kEsz;
   const uint8_t* X = static_cast<const uint8_t*>(a.x);
   const uint8_t* Y = static_cast<const uint8_t*>(a.y);
   const int64_t ldxb = a.ldx * TR::kEsz, ldyb = a.ldy * TR::kEsz;
   const int nslab = int(ceil_div(Kb, kSlabBytes));
 
-  typename TR::accv_t acc[MI][NJ];
+  typename TR::accv_t acc;
 #pragma unroll
-  for (int m = 0; m < MI; ++m)
-#pragma unroll
-    for (int n = 0; n < NJ; ++n)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[m][n][v] = 0;
+  for (int v = 0; v < 16; ++v) acc[v] = 0;
 
   i32x4 xr[XCH], yr[YCH];
   auto load_slab = [&](int slab) {
@@ -74,12 +97,12 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs a) {
 #pragma unroll
     for (int r = 0; r < XCH; ++r) {
       const int c = tid + 256 * r, row = c >> 3, kc = c & 7;
-      xr[r] = load_chunk<VEC>(X + (i0 + row) * ldxb, k0 + kc * 16, Kb, i0 + row < a.I);
+      xr[r] = load_chunk_checked<VEC>(X + (i0 + row) * ldxb, k0 + kc * 16, Kb, i0 + row < a.I);
     }
 #pragma unroll
     for (int r = 0; r < YCH; ++r) {
       const int c = tid + 256 * r, row = c >> 3, kc = c & 7;
-      yr[r] = load_chunk<VEC>(Y + (j0 + row) * ldyb, k0 + kc * 16, Kb, j0 + row < a.J);
+      yr[r] = load_chunk_checked<VEC>(Y + (j0 + row) * ldyb, k0 + kc * 16, Kb, j0 + row < a.J);
     }
   };
   auto store_slab = [&](int buf) {
@@ -100,52 +123,155 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs a) {
   load_slab(0);
   store_slab(0);
   __syncthreads();
+  const int frag_off = (lane & 31) * kRowBytes + (lane >> 5) * 16;
   for (int slab = 0; slab < nslab; ++slab) {
     if (slab + 1 < nslab) load_slab(slab + 1);
-    const uint8_t* xs = lds + (slab & 1) * kBuf;
-    const uint8_t* ys = xs + kXBytes;
-    const int frag_off = (lane & 31) * kRowBytes + (lane >> 5) * 16;
+    const uint8_t* xs = lds + (slab & 1) * kBuf + wm * 32 * kRowBytes + frag_off;
+    const uint8_t* ys = lds + (slab & 1) * kBuf + kXBytes + wn * 32 * kRowBytes + frag_off;
 #pragma unroll
-    for (int ks = 0; ks < kSlabBytes / 32; ++ks) {
+    for (int ks = 0; ks < kSlabBytes / 32; ++ks)
+      acc = TR::mfma(*reinterpret_cast<const i32x4*>(xs + ks * 32),
+                     *reinterpret_cast<const i32x4*>(ys + ks * 32), acc);
+    if (slab + 1 < nslab) store_slab((slab + 1) & 1);
+    __syncthreads();
+  }
+
+  const int64_t j = j0 + wn * 32 + (lane & 31);
+  if (j < a.J) {
+    const int64_t jbase = (j / a.jp) * (a.I * a.jp) + (j % a.jp);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int64_t i = i0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (i < a.I)
+        store_result<typename TR::acc_t>(a.out, a.residual, a.out_dtype, jbase + i * a.jp, acc[v],
+                                         a.relu);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Direct-to-LDS kernel.  LDS slab layout: row r at r*128 bytes, 16-byte column c of that row at
+// position c ^ (r & 7).  One global_load_lds instruction fills 8 rows: lane i lands at
+// (row i/8, position i%8) and therefore fetches global column (i%8) ^ (i/8).
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <typename TR, int BM, int BN, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a) {
+  constexpr int NW = WGM * WGN;                   // waves per workgroup
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
+  constexpr int MI = WM / 32, NJ = WN / 32;       // 32x32 MFMA blocks per wave
+  constexpr int XQ = BM / 8 / NW, YQ = BN / 8 / NW;   // 8-row load instructions per wave per slab
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
+  constexpr int kXBytes = BM * kSlabBytes, kYBytes = BN * kSlabBytes;
+  constexpr int kBuf = kXBytes + kYBytes;
+  constexpr int KS = kSlabBytes / 32;             // MFMA K steps per slab
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int64_t tiles_i = ceil_div(a.I, BM), tiles_j = ceil_div(a.J, BN);
+  int64_t ti, tj;
+  tile_of_block(blockIdx.x, gridDim.x, tiles_i, tiles_j, &ti, &tj);
+  const int64_t i0 = ti * BM, j0 = tj * BN;
+
+  const uint8_t* X = static_cast<const uint8_t*>(a.x);
+  const uint8_t* Y = static_cast<const uint8_t*>(a.y);
+  const int64_t ldxb = a.ldx * TR::kEsz, ldyb = a.ldy * TR::kEsz;
+  const int nslab = int(a.K * TR::kEsz / kSlabBytes);
+
+  // Global source of each of this lane's load instructions (rows past the end are clamped: their
+  // products land in accumulators that are never stored).
+  const int lrow = lane >> 3, lcol = ((lane & 7) ^ lrow) * 16;
+  const uint8_t* xsrc[XQ];
+  const uint8_t* ysrc[YQ];
+#pragma unroll
+  for (int q = 0; q < XQ; ++q) {
+    int64_t row = i0 + (wave + q * NW) * 8 + lrow;
+    row = row < a.I ? row : a.I - 1;
+    xsrc[q] = X + row * ldxb + lcol;
+  }
+#pragma unroll
+  for (int q = 0; q < YQ; ++q) {
+    int64_t row = j0 + (wave + q * NW) * 8 + lrow;
+    row = row < a.J ? row : a.J - 1;
+    ysrc[q] = Y + row * ldyb + lcol;
+  }
+  auto issue_slab = [&](int slab, int buf) {
+    const int64_t k0 = int64_t(slab) * kSlabBytes;
+    uint8_t* xs = lds + buf * kBuf + wave * 1024;
+    uint8_t* ys = xs + kXBytes;
+#pragma unroll
+    for (int q = 0; q < XQ; ++q)
+      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc[q] + k0), (lptr_t)(xs + q * NW * 1024), 16, 0, 0);
+#pragma unroll
+    for (int q = 0; q < YQ; ++q)
+      __builtin_amdgcn_global_load_lds((gptr_t)(ysrc[q] + k0), (lptr_t)(ys + q * NW * 1024), 16, 0, 0);
+  };
+
+  typename TR::accv_t acc[MI][NJ];
+  static_for<MI>([&](auto m_) {
+    static_for<NJ>([&](auto n_) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[decltype(m_)::value][decltype(n_)::value][v] = 0;
+    });
+  });
+
+  // Fragment addresses: row (lane % 32) of a 32-row block, column 2*ks + lane/32, swizzled.
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) koff[ks] = (((2 * ks + (lane >> 5)) ^ (lane & 7)) << 4);
+  const int xrow = (wm * WM + (lane & 31)) * kSlabBytes;
+  const int yrow = kXBytes + (wn * WN + (lane & 31)) * kSlabBytes;
+
+  issue_slab(0, 0);
+  __syncthreads();
+  for (int slab = 0; slab < nslab; ++slab) {
+    if (slab + 1 < nslab) issue_slab(slab + 1, (slab + 1) & 1);
+    const uint8_t* base = lds + (slab & 1) * kBuf;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
       i32x4 af[MI], bf[NJ];
 #pragma unroll
       for (int m = 0; m < MI; ++m)
-        af[m] = *reinterpret_cast<const i32x4*>(xs + (wm * WM + m * 32) * kRowBytes + frag_off + ks * 32);
+        af[m] = *reinterpret_cast<const i32x4*>(base + xrow + m * 32 * kSlabBytes + koff[ks]);
 #pragma unroll
       for (int n = 0; n < NJ; ++n)
-        bf[n] = *reinterpret_cast<const i32x4*>(ys + (wn * WN + n * 32) * kRowBytes + frag_off + ks * 32);
+        bf[n] = *reinterpret_cast<const i32x4*>(base + yrow + n * 32 * kSlabBytes + koff[ks]);
 #pragma unroll
       for (int m = 0; m < MI; ++m)
 #pragma unroll
         for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(af[m], bf[n], acc[m][n]);
     }
-    if (slab + 1 < nslab) store_slab((slab + 1) & 1);
-    __syncthreads();
+    __syncthreads();   // next slab has landed (the barrier waits for this wave's loads) and
+                       // every wave is done reading the current one
   }
 
   // Epilogue: lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each block.
-#pragma unroll
-  for (int n = 0; n < NJ; ++n) {
+  static_for<NJ>([&](auto n_) {
+    constexpr int n = decltype(n_)::value;
     const int64_t j = j0 + wn * WN + n * 32 + (lane & 31);
-    if (j >= a.J) continue;
+    const bool j_ok = j < a.J;
     const int64_t jbase = (j / a.jp) * (a.I * a.jp) + (j % a.jp);
-#pragma unroll
-    for (int m = 0; m < MI; ++m) {
+    static_for<MI>([&](auto m_) {
+      constexpr int m = decltype(m_)::value;
+      const int64_t ibase = i0 + wm * WM + m * 32 + 4 * (lane >> 5);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int64_t i = i0 + wm * WM + m * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (i < a.I)
+        const int64_t i = ibase + 8 * (v >> 2) + (v & 3);
+        if (j_ok && i < a.I)
           store_result<typename TR::acc_t>(a.out, a.residual, a.out_dtype, jbase + i * a.jp,
                                            acc[m][n][v], a.relu);
       }
-    }
-  }
+    });
+  });
 }
 
-template <typename TR, int BM, int BN, bool VEC>
-static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
-  constexpr int lds_bytes = 2 * (BM + BN) * kRowBytes;
-  auto kern = gemm_nt_kernel<TR, BM, BN, VEC>;
+template <typename TR, int BM, int BN, int WGM, int WGN>
+static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
+  constexpr int lds_bytes = 2 * (BM + BN) * kSlabBytes;
+  auto kern = gemm_nt_dma_kernel<TR, BM, BN, WGM, WGN>;
   static bool attr_done = false;   // benign race: the attribute call is idempotent
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -154,7 +280,7 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s) {
     attr_done = true;
   }
   const int64_t tiles = ceil_div(a.I, BM) * ceil_div(a.J, BN);
-  hipLaunchKernelGGL(kern, dim3(unsigned(tiles)), dim3(256), lds_bytes, s, a);
+  hipLaunchKernelGGL(kern, dim3(unsigned(tiles)), dim3(WGM * WGN * 64), lds_bytes, s, a);
   return hipGetLastError();
 }
 
@@ -163,10 +289,34 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
   const bool vec = (a.ldx * TR::kEsz) % 16 == 0 && (a.ldy * TR::kEsz) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.x) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.y) % 16 == 0;
-  // Small problems take 64x64 tiles so that more compute units get work.
-  const bool small = ceil_div(a.I, 128) * ceil_div(a.J, 128) < 256;
-  if (vec) return small ? launch_cfg<TR, 64, 64, true>(a, s) : launch_cfg<TR, 128, 128, true>(a, s);
-  return small ? launch_cfg<TR, 64, 64, false>(a, s) : launch_cfg<TR, 128, 128, false>(a, s);
+  const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % kSlabBytes == 0;
+  if (dma) {
+    if (const char* e = getenv("GS_GEMM_CFG")) {   // TUNING ONLY
+      switch (atoi(e)) {
+        case 1: return launch_dma<TR, 256, 256, 2, 2>(a, s);
+        case 2: return launch_dma<TR, 256, 256, 2, 4>(a, s);
+        case 3: return launch_dma<TR, 256, 128, 2, 2>(a, s);
+        case 4: return launch_dma<TR, 256, 128, 4, 2>(a, s);
+        case 5: return launch_dma<TR, 128, 128, 2, 2>(a, s);
+        case 6: return launch_dma<TR, 128, 256, 2, 4>(a, s);
+        case 7: return launch_dma<TR, 128, 128, 2, 4>(a, s);
+        case 8: return launch_dma<TR, 64, 64, 2, 2>(a, s);
+        case 9: return launch_dma<TR, 256, 256, 4, 4>(a, s);
+        case 10: return launch_dma<TR, 256, 128, 4, 4>(a, s);
+      }
+    }
+    const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
+    const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);
+    if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4>(a, s);
+    if (t128 >= 192) return launch_dma<TR, 128, 128, 2, 2>(a, s);
+    return launch_dma<TR, 64, 64, 2, 2>(a, s);
+  }
+  const int64_t tiles = ceil_div(a.I, 64) * ceil_div(a.J, 64);
+  if (vec)
+    hipLaunchKernelGGL((gemm_nt_checked_kernel<TR, true>), dim3(unsigned(tiles)), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((gemm_nt_checked_kernel<TR, false>), dim3(unsigned(tiles)), dim3(256), 0, s, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
