@@ -34,9 +34,20 @@ __device__ __forceinline__ void static_for(F&& f) {
 // load of the wave, which would drain software prefetches that are meant to stay in flight
 // across the barrier; this one waits for LDS operations alone.
 __device__ __forceinline__ void lds_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  // Written as one asm block: a compiler-level fence would also wait for every outstanding
+  // global_load_lds transfer (they write LDS), which is exactly what must stay in flight.
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+// 16 bytes per lane, global -> LDS, without passing through registers: lane i of the wave lands at
+// lds_base + 16 i (lds_base must be wave-uniform).  Written as asm rather than through the
+// compiler builtin on purpose: the compiler orders every later LDS access after a builtin
+// transfer by waiting for ALL outstanding vector-memory loads, which would also drain register
+// prefetches that are meant to stay in flight.  The caller must wait for the transfer itself
+// (wait_vmem) and synchronise before any wave reads the bytes.
+__device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_base) {
+  const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(gptr), "s"(base) : "memory", "m0");
 }
 // Wait until at most N of this wave's vector-memory loads (which complete in order) are still
 // outstanding.  N above the counter's range waits for more than necessary, never less.
@@ -45,8 +56,58 @@ __device__ __forceinline__ void wait_vmem() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N < 63 ? N : 63) : "memory");
 }
 
+// Hand-ordered LDS reads.  Left to itself the compiler emits "read fragments, wait, MFMAs" per
+// K step, which puts the whole LDS latency in front of every group of MFMAs when a SIMD holds a
+// single wave.  `lds_read_pinned` is an `asm volatile` read that stays where it is written, and
+// `lds_wait_tied<N>(regs...)` waits until at most N LDS requests are outstanding (a wave's LDS
+// requests complete in order) and makes every later use of `regs` depend on that wait, so code
+// can request the fragments of step k+1, wait for those of step k only, and issue its MFMAs.
+__device__ __forceinline__ void lds_read_pinned(i32x4& dst, uint32_t lds_byte_addr) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(lds_byte_addr) : "memory");
+}
+template <int N, int COUNT>
+__device__ __forceinline__ void lds_wait_tied(i32x4* regs) {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N < 15 ? N : 15) : "memory");
+#pragma unroll
+  for (int i = 0; i < COUNT; ++i) asm volatile("" : "+v"(regs[i]));
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return uint32_t(uintptr_t((const __attribute__((address_space(3))) uint8_t*)p));
+}
+
 __host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 __host__ __device__ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+// Division of 31-bit unsigned numbers by a run-time constant as multiply-high and shift (integer
+// division is a ~40-instruction routine on this hardware).  With l = ceil(log2 d) and
+// m = floor(2^(31+l) / d) + 1, floor(x / d) = (x * m) >> (31 + l) for every x < 2^31.
+struct FastDiv {
+  uint32_t d, mul, shift;   // shift = l - 1 applied to the high word; d == 1 is special-cased
+  __host__ __device__ static FastDiv make(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((uint64_t(1) << l) < d) ++l;
+    f.mul = d > 1 ? uint32_t(((uint64_t(1) << (31 + l)) / d) + 1) : 0;
+    f.shift = l > 0 ? l - 1 : 0;
+    return f;
+  }
+  __device__ __forceinline__ uint32_t div(uint32_t x) const {
+    return d == 1 ? x : (__umulhi(x, mul) >> shift);
+  }
+  __device__ __forceinline__ void divmod(uint32_t x, uint32_t* q, uint32_t* r) const {
+    *q = div(x);
+    *r = x - *q * d;
+  }
+};
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// Two floats -> two bfloat16 (round to nearest even) packed in one dword, low half first.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 __host__ __device__ inline size_t dtype_size(int dt) {
   return dt == GS_I8 ? 1 : dt == GS_BF16 ? 2 : 4;

@@ -13,7 +13,10 @@ static hipError_t launch_conv3_cfg(const ConvArgs& a, ConvGeom g, hipStream_t s)
   if (g.max_rows < 0) return hipErrorInvalidValue;
   const int64_t items = int64_t(g.max_rows) * (a.W / VW) * 2;
   if (items > 256 * MAXI) return hipErrorInvalidValue;
-  const size_t lds_bytes = 1024 + 3 * size_t(a.Kh * a.Kw) * TO * 32 + 2 * size_t(g.max_rows) * g.PW * 48;
+  const size_t stage_bytes = 4 * 32 * size_t(TP / WP * 4 + 16);   // epilogue staging, one region per wave
+  size_t patch_bytes = 2 * size_t(g.max_rows) * g.PW * 48;
+  if (patch_bytes < stage_bytes) patch_bytes = stage_bytes;
+  const size_t lds_bytes = 1024 + 3 * size_t(a.Kh * a.Kw) * TO * 32 + patch_bytes;
   if (lds_bytes > size_t(kLdsLimit)) return hipErrorInvalidValue;
   auto kern = conv_direct3_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, D>;
   static bool attr_done = false;
@@ -34,7 +37,6 @@ template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW>
 static hipError_t launch_conv3_depth(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
   const int nchunk = a.Cpad / (32 / TR::kEsz);
   if (nchunk < 2) return hipErrorInvalidValue;
-  if (nchunk % 4 == 0) return launch_conv3_cfg<TR, TO, TP, WO, WP, VW, KH, KW, 4>(a, g, s);
   if (nchunk % 2 == 0) return launch_conv3_cfg<TR, TO, TP, WO, WP, VW, KH, KW, 2>(a, g, s);
   return hipErrorInvalidValue;   // odd chunk counts take the general kernel
 }

@@ -291,20 +291,6 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
                    reinterpret_cast<uintptr_t>(a.y) % 16 == 0;
   const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % kSlabBytes == 0;
   if (dma) {
-    if (const char* e = getenv("GS_GEMM_CFG")) {   // TUNING ONLY
-      switch (atoi(e)) {
-        case 1: return launch_dma<TR, 256, 256, 2, 2>(a, s);
-        case 2: return launch_dma<TR, 256, 256, 2, 4>(a, s);
-        case 3: return launch_dma<TR, 256, 128, 2, 2>(a, s);
-        case 4: return launch_dma<TR, 256, 128, 4, 2>(a, s);
-        case 5: return launch_dma<TR, 128, 128, 2, 2>(a, s);
-        case 6: return launch_dma<TR, 128, 256, 2, 4>(a, s);
-        case 7: return launch_dma<TR, 128, 128, 2, 4>(a, s);
-        case 8: return launch_dma<TR, 64, 64, 2, 2>(a, s);
-        case 9: return launch_dma<TR, 256, 256, 4, 4>(a, s);
-        case 10: return launch_dma<TR, 256, 128, 4, 4>(a, s);
-      }
-    }
     const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
     const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);
     if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4>(a, s);

@@ -1,12 +1,7 @@
 // `windows` transformer (Table 1) as an explicit gather: out[a, p.., q..] = in[a, p_i*s_i+q_i-lo_i ..].
 //
-// Two kernels:
-//   windows_generic : any 1..4 compute dims, one output element per thread, consecutive threads
-//                     write consecutive output elements (coalesced stores, cached gathers).
-//   windows_chw     : the convolution shape, in ((N),(C,H,W)), window (C,Kh,Kw), strides (1,Sh,Sw).
-//                     A workgroup owns a band of output rows of one image, stages the input rows
-//                     it needs (with halo) in LDS with coalesced row reads, and writes the window
-//                     rows as one contiguous run of 16-byte stores.
+// windows_generic : any 1..4 compute dims, one output element per thread, consecutive threads
+//                   write consecutive output elements (coalesced stores, cached gathers).
 #include "common.h"
 
 namespace gs {
