@@ -15,18 +15,22 @@ template <typename T> struct Elem;
 template <> struct Elem<int8_t> {
   using acc = int32_t;
   __device__ static acc load(const int8_t* p, int64_t i) { return p[i]; }
+  __device__ static acc cvt(int8_t v) { return v; }
 };
 template <> struct Elem<int32_t> {
   using acc = int32_t;
   __device__ static acc load(const int32_t* p, int64_t i) { return p[i]; }
+  __device__ static acc cvt(int32_t v) { return v; }
 };
 template <> struct Elem<float> {
   using acc = float;
   __device__ static acc load(const float* p, int64_t i) { return p[i]; }
+  __device__ static acc cvt(float v) { return v; }
 };
 template <> struct Elem<uint16_t> {  // bfloat16 bits
   using acc = float;
   __device__ static acc load(const uint16_t* p, int64_t i) { return bf16_bits_to_float(p[i]); }
+  __device__ static acc cvt(uint16_t v) { return bf16_bits_to_float(v); }
 };
 
 template <typename A> __device__ inline A ident(int op);
@@ -180,12 +184,356 @@ static hipError_t launch_windows_reduce_t(const WindowsReduceArgs& a, hipStream_
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// compute reduce (windows in w s) over the last two dims (pooling, Fig. 2c), staged through LDS.
+// A workgroup owns a band of output rows of one plane: it copies the input rows the band needs
+// into LDS with coalesced 16-byte reads (padding cells hold the operator's identity), then every
+// thread folds whole windows out of LDS, so each input byte leaves HBM once however much the
+// windows overlap.  KH / KW fix the window at compile time (0 = run-time loops).
+// ---------------------------------------------------------------------------------------------
+struct Pool2dArgs {
+  const void* in;
+  void* out;
+  int out_dtype, op;
+  int H, W, Ho, Wo, Kh, Kw, Sh, Sw, Ph, Pw;
+  int HB;          // output rows per band
+  int bands;       // bands per plane
+  int rows;        // LDS rows per band: (HB - 1) * Sh + Kh
+  int pitch, XO;   // LDS row pitch and first data column, in elements
+  int64_t tasks;   // planes * bands
+  float scale;
+  int G;           // groups of VO outputs per output row (vector kernel)
+  int rows_alloc;  // LDS rows allocated
+  FastDiv dvpr, dW, dhalo, dWo, dG;
+};
+
+constexpr int kPoolLdsBudget = 32 * 1024;
+
+template <typename T> __device__ inline T ident_elem(int op);
+template <> __device__ inline int8_t ident_elem<int8_t>(int op) { return op == GS_MAX ? int8_t(-128) : int8_t(0); }
+template <> __device__ inline int32_t ident_elem<int32_t>(int op) { return op == GS_MAX ? INT_MIN : 0; }
+template <> __device__ inline float ident_elem<float>(int op) { return op == GS_MAX ? -INFINITY : 0.0f; }
+template <> __device__ inline uint16_t ident_elem<uint16_t>(int op) { return op == GS_MAX ? uint16_t(0xff80) : uint16_t(0); }
+
+// Copies the input rows of one band into LDS; cells outside the image hold the identity.
+template <typename T>
+__device__ __forceinline__ void pool2d_stage(const Pool2dArgs& a, T* stage, const T* src, int ih0,
+                                             int nrows, int tid) {
+  constexpr int ESZ = int(sizeof(T));
+  constexpr int EPV = 16 / ESZ;
+  typedef T vec_t __attribute__((ext_vector_type(EPV)));
+  const T idv = ident_elem<T>(a.op);
+  const bool vec_ok = (a.W * ESZ) % 16 == 0 && reinterpret_cast<uintptr_t>(a.in) % 16 == 0;
+  const int vpr = a.W * ESZ / 16;
+  const int halo = a.pitch - a.W;
+  if (vec_ok) {
+    // Loads are issued kBatch at a time before any is stored: one memory latency per batch.
+    constexpr int kBatch = 8;
+    vec_t idvec;
+#pragma unroll
+    for (int i = 0; i < EPV; ++i) idvec[i] = idv;
+    const int nvec = nrows * vpr;
+    for (int base = 0; base < nvec; base += 256 * kBatch) {
+      vec_t val[kBatch];
+      int dst[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int id = base + u * 256 + tid;
+        uint32_t r, v;
+        a.dvpr.divmod(uint32_t(id), &r, &v);
+        const int ih = ih0 + int(r);
+        dst[u] = id < nvec ? int(r) * a.pitch + a.XO + int(v) * EPV : -1;
+        val[u] = idvec;
+        if (id < nvec && ih >= 0 && ih < a.H)
+          val[u] = *reinterpret_cast<const vec_t*>(src + int64_t(ih) * a.W + int(v) * EPV);
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        if (dst[u] >= 0) *reinterpret_cast<vec_t*>(stage + dst[u]) = val[u];
+    }
+  } else {
+    for (int id = tid; id < nrows * a.W; id += 256) {
+      uint32_t r, x;
+      a.dW.divmod(uint32_t(id), &r, &x);
+      const int ih = ih0 + int(r);
+      stage[int(r) * a.pitch + a.XO + int(x)] = (ih >= 0 && ih < a.H) ? src[int64_t(ih) * a.W + int(x)] : idv;
+    }
+  }
+  for (int id = tid; id < nrows * halo; id += 256) {
+    uint32_t r, h;
+    a.dhalo.divmod(uint32_t(id), &r, &h);
+    stage[int(r) * a.pitch + (int(h) < a.XO ? int(h) : a.W + int(h))] = idv;
+  }
+}
+
+// Any window: one output per thread and step, run-time window loops.
+template <typename T>
+__global__ void __launch_bounds__(256)
+pool2d_kernel(Pool2dArgs a) {
+  using A = typename Elem<T>::acc;
+  extern __shared__ __attribute__((aligned(16))) uint8_t pool_lds[];
+  T* stage = reinterpret_cast<T*>(pool_lds);
+  const int tid = threadIdx.x;
+  for (int64_t task = blockIdx.x; task < a.tasks; task += gridDim.x) {
+    const int64_t plane = task / a.bands;
+    const int band = int(task - plane * a.bands);
+    const int ho0 = band * a.HB;
+    const int nho = a.Ho - ho0 < a.HB ? a.Ho - ho0 : a.HB;
+    const int nrows = (nho - 1) * a.Sh + a.Kh;
+    if (task != int64_t(blockIdx.x)) __syncthreads();
+    pool2d_stage<T>(a, stage, static_cast<const T*>(a.in) + plane * a.H * a.W, ho0 * a.Sh - a.Ph, nrows, tid);
+    __syncthreads();
+    const int64_t obase = (plane * a.Ho + ho0) * a.Wo;
+    const int items = nho * a.Wo;
+    for (int id = tid; id < items; id += 256) {
+      uint32_t hl, y;
+      a.dWo.divmod(uint32_t(id), &hl, &y);
+      const T* w0 = stage + int(hl) * a.Sh * a.pitch + a.XO - a.Pw + int(y) * a.Sw;
+      A acc = ident<A>(a.op);
+      for (int dx = 0; dx < a.Kh; ++dx)
+        for (int dy = 0; dy < a.Kw; ++dy) acc = combine(acc, Elem<T>::load(w0, dx * a.pitch + dy), a.op);
+      store_out<A>(a.out, a.out_dtype, obase + id, finish(acc, a.scale));
+    }
+  }
+}
+
+// Compile-time window, stride and left padding, input rows that are whole 16-byte vectors.
+// Persistent workgroups walk over (plane, band) tasks; while one task is folded out of LDS the
+// 16-byte loads of the next are in flight into registers.  A thread produces VO = EPV / SW
+// neighbouring outputs of one output row from aligned 16-byte LDS reads (plus the PW elements in
+// front of them): it converts each element once, folds the KH rows element-wise, then the KW
+// neighbours of every output.
+template <typename T, int KH, int KW, int SH, int SW, int PW, bool ISMAX, int B>
+__global__ void __launch_bounds__(256)
+pool2d_vec_kernel(Pool2dArgs a) {
+  using A = typename Elem<T>::acc;
+  constexpr int ESZ = int(sizeof(T));
+  constexpr int EPV = 16 / ESZ;
+  constexpr int VO = EPV / SW;                      // outputs per thread and step
+  constexpr int NEED = (VO - 1) * SW + KW - PW;     // elements from the aligned boundary on
+  constexpr int NVF = NEED / EPV, TAIL = NEED % EPV;
+  constexpr int SPAN = PW + NEED;
+  constexpr int OP = ISMAX ? GS_MAX : GS_SUM;
+  typedef T vec_t __attribute__((ext_vector_type(EPV)));
+  extern __shared__ __attribute__((aligned(16))) uint8_t pool_lds[];
+  T* stage = reinterpret_cast<T*>(pool_lds);
+  const int tid = threadIdx.x;
+  const T idv = ident_elem<T>(OP);
+  vec_t idvec;
+#pragma unroll
+  for (int i = 0; i < EPV; ++i) idvec[i] = idv;
+  const int vpr = a.W * ESZ / 16;
+  const int halo = a.pitch - a.W;
+  const bool out_native = a.out_dtype == (__is_same(T, int8_t) ? GS_I8 : __is_same(T, int32_t) ? GS_I32
+                                          : __is_same(T, uint16_t) ? GS_BF16 : GS_F32);
+  const bool vec_store = out_native && a.Wo % VO == 0 &&
+                         reinterpret_cast<uintptr_t>(a.out) % (VO * ESZ) == 0;
+
+  vec_t val[B];
+  auto issue_loads = [&](int64_t task) {
+    const int64_t plane = task / a.bands;
+    const int band = int(task - plane * a.bands);
+    const int ho0 = band * a.HB;
+    const int nho = a.Ho - ho0 < a.HB ? a.Ho - ho0 : a.HB;
+    const int nvec = ((nho - 1) * SH + KH) * vpr;
+    const int ih0 = ho0 * SH - a.Ph;
+    const T* src = static_cast<const T*>(a.in) + plane * a.H * a.W;
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      const int id = u * 256 + tid;
+      uint32_t r, v;
+      a.dvpr.divmod(uint32_t(id), &r, &v);
+      const int ih = ih0 + int(r);
+      val[u] = idvec;
+      if (id < nvec && ih >= 0 && ih < a.H)
+        val[u] = *reinterpret_cast<const vec_t*>(src + int64_t(ih) * a.W + int(v) * EPV);
+    }
+  };
+
+  int64_t task = blockIdx.x;
+  if (task >= a.tasks) return;
+  for (int id = tid; id < a.rows_alloc * halo; id += 256) {   // padding cells, written once
+    uint32_t r, h;
+    a.dhalo.divmod(uint32_t(id), &r, &h);
+    stage[int(r) * a.pitch + (int(h) < a.XO ? int(h) : a.W + int(h))] = idv;
+  }
+  issue_loads(task);
+  for (; task < a.tasks; task += gridDim.x) {
+    const int64_t plane = task / a.bands;
+    const int band = int(task - plane * a.bands);
+    const int ho0 = band * a.HB;
+    const int nho = a.Ho - ho0 < a.HB ? a.Ho - ho0 : a.HB;
+    const int nvec = ((nho - 1) * SH + KH) * vpr;
+    __syncthreads();                                 // the previous task has been folded
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      const int id = u * 256 + tid;
+      if (id < nvec) {
+        uint32_t r, v;
+        a.dvpr.divmod(uint32_t(id), &r, &v);
+        *reinterpret_cast<vec_t*>(stage + int(r) * a.pitch + a.XO + int(v) * EPV) = val[u];
+      }
+    }
+    __syncthreads();
+    if (task + gridDim.x < a.tasks) issue_loads(task + gridDim.x);
+    const int64_t obase = (plane * a.Ho + ho0) * a.Wo;
+    const int items = nho * a.G;
+    for (int id = tid; id < items; id += 256) {
+      uint32_t hl, g;
+      a.dG.divmod(uint32_t(id), &hl, &g);
+      // element (dx, c) of the span: LDS row hl*SH + dx, column XO + g*EPV - PW + c
+      const T* base = stage + int(hl) * SH * a.pitch + a.XO + int(g) * EPV;
+      A col[SPAN];
+      static_for<KH>([&](auto dx) {
+        const T* row = base + dx * a.pitch;
+        A e[SPAN];
+        static_for<PW>([&](auto c) { e[c] = Elem<T>::load(row, int(c) - PW); });
+        static_for<NVF>([&](auto q) {
+          const vec_t v = *reinterpret_cast<const vec_t*>(row + q * EPV);
+          static_for<EPV>([&](auto i) { e[PW + q * EPV + i] = Elem<T>::cvt(v[int(i)]); });
+        });
+        static_for<TAIL>([&](auto c) { e[PW + NVF * EPV + c] = Elem<T>::load(row, NVF * EPV + c); });
+        static_for<SPAN>([&](auto c) {
+          if constexpr (decltype(dx)::value == 0) col[c] = e[c];
+          else col[c] = combine(col[c], e[c], OP);
+        });
+      });
+      A res[VO];
+      static_for<VO>([&](auto v) {
+        A acc = col[v * SW];
+        static_for<KW - 1>([&](auto dy) { acc = combine(acc, col[v * SW + dy + 1], OP); });
+        res[v] = acc;
+      });
+      const int y0 = int(g) * VO;
+      const int64_t o = obase + int64_t(hl) * a.Wo + y0;
+      if (vec_store) {
+        typedef T ovec_t __attribute__((ext_vector_type(VO)));
+        ovec_t ov;
+        static_for<VO>([&](auto v) {
+          if constexpr (__is_same(T, uint16_t)) {
+            // a maximum is one of the inputs: its bfloat16 bits are the high half, no rounding
+            ov[int(v)] = ISMAX ? uint16_t(__float_as_uint(res[v]) >> 16) : float_to_bf16_bits(finish(res[v], a.scale));
+          } else {
+            ov[int(v)] = T(finish(res[v], a.scale));
+          }
+        });
+        *reinterpret_cast<ovec_t*>(static_cast<T*>(a.out) + o) = ov;
+      } else {
+        static_for<VO>([&](auto v) {
+          if (y0 + v < a.Wo) store_out<A>(a.out, a.out_dtype, o + v, finish(res[v], a.scale));
+        });
+      }
+    }
+  }
+}
+
+static int pool_num_cus() {
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
+}
+
+template <typename T>
+static hipError_t launch_pool2d_t(const WindowsReduceArgs& w, hipStream_t s) {
+  constexpr int ESZ = int(sizeof(T));
+  constexpr int EPV = 16 / ESZ;
+  if (w.n_compute != 2) return hipErrorInvalidValue;
+  for (int d = 0; d < 2; ++d)
+    if (w.in_dim[d] > (1 << 20) || w.out_dim[d] > (1 << 20) || w.win[d] > (1 << 12) ||
+        w.stride[d] > (1 << 12) || w.pad_lo[d] > (1 << 12) || w.out_dim[d] < 1)
+      return hipErrorInvalidValue;
+  Pool2dArgs a;
+  a.in = w.in; a.out = w.out; a.out_dtype = w.out_dtype; a.op = w.op; a.scale = w.scale;
+  a.H = int(w.in_dim[0]); a.W = int(w.in_dim[1]);
+  a.Ho = int(w.out_dim[0]); a.Wo = int(w.out_dim[1]);
+  a.Kh = int(w.win[0]); a.Kw = int(w.win[1]);
+  a.Sh = int(w.stride[0]); a.Sw = int(w.stride[1]);
+  a.Ph = int(w.pad_lo[0]); a.Pw = int(w.pad_lo[1]);
+  a.XO = int(round_up(a.Pw, EPV));
+  const int64_t reach = int64_t(a.XO) - a.Pw + int64_t(a.Wo - 1) * a.Sw + a.Kw;
+  const int64_t width = reach > a.XO + a.W ? reach : a.XO + a.W;
+  // one spare vector per row: the last group of outputs of a row may read past the last window
+  a.pitch = int(round_up(width + EPV, EPV));
+  const int64_t row_bytes = int64_t(a.pitch) * ESZ;
+  const int64_t max_rows = kPoolLdsBudget / row_bytes;
+  if (max_rows < a.Kh) return hipErrorInvalidValue;
+  int64_t hb = (max_rows - a.Kh) / a.Sh + 1;
+  if (hb > a.Ho) hb = a.Ho;
+  a.bands = int(ceil_div(a.Ho, hb));
+  a.HB = int(ceil_div(a.Ho, a.bands));
+  a.rows = (a.HB - 1) * a.Sh + a.Kh;
+  a.tasks = w.outer * a.bands;
+  if (a.tasks == 0) return hipSuccess;
+  if (int64_t(a.H) * a.W > (int64_t(1) << 40) / (w.outer > 0 ? w.outer : 1)) return hipErrorInvalidValue;
+  a.dvpr = FastDiv::make(uint32_t(a.W * ESZ / 16 > 0 ? a.W * ESZ / 16 : 1));
+  a.dW = FastDiv::make(uint32_t(a.W > 0 ? a.W : 1));
+  a.dhalo = FastDiv::make(uint32_t(a.pitch - a.W > 0 ? a.pitch - a.W : 1));
+  a.dWo = FastDiv::make(uint32_t(a.Wo));
+  a.rows_alloc = a.rows;
+  a.G = 1;
+  a.dG = FastDiv::make(1);
+  const size_t lds = size_t(a.rows) * row_bytes;
+  if (lds > 60 * 1024) return hipErrorInvalidValue;
+  const bool is_max = a.op == GS_MAX;
+  const bool vec_in = (a.W * ESZ) % 16 == 0 && reinterpret_cast<uintptr_t>(a.in) % 16 == 0;
+  const int64_t need = ceil_div(int64_t(a.rows) * (a.W * ESZ / 16), 256);
+  // Persistent grid for the vector kernels: what the chip holds at once, by LDS.
+  int per_cu = int((160 * 1024) / (lds + 512));
+  per_cu = per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu;
+  int64_t pgrid = int64_t(pool_num_cus()) * per_cu;
+  if (pgrid > a.tasks) pgrid = a.tasks;
+#define GS_POOL_VEC(KH_, KW_, SH_, SW_, PW_)                                                        \
+  if (vec_in && need <= 8 && a.Kh == KH_ && a.Kw == KW_ && a.Sh == SH_ && a.Sw == SW_ &&           \
+      a.Pw == PW_ && EPV % SW_ == 0) {                                                             \
+    constexpr int VO_ = EPV / SW_ > 0 ? EPV / SW_ : 1;                                             \
+    constexpr int NEED_ = (VO_ - 1) * SW_ + KW_ - PW_;                                             \
+    Pool2dArgs v = a;                                                                              \
+    v.G = int(ceil_div(a.Wo, VO_));                                                                \
+    v.dG = FastDiv::make(uint32_t(v.G));                                                           \
+    const int64_t wide = int64_t(v.XO) + int64_t(v.G - 1) * EPV + NEED_;                           \
+    if (wide <= a.pitch) {                                                                         \
+      if (need <= 4) {                                                                             \
+        if (is_max) hipLaunchKernelGGL((pool2d_vec_kernel<T, KH_, KW_, SH_, SW_, PW_, true, 4>),   \
+                                       dim3(unsigned(pgrid)), dim3(256), lds, s, v);               \
+        else hipLaunchKernelGGL((pool2d_vec_kernel<T, KH_, KW_, SH_, SW_, PW_, false, 4>),         \
+                                dim3(unsigned(pgrid)), dim3(256), lds, s, v);                      \
+      } else {                                                                                     \
+        if (is_max) hipLaunchKernelGGL((pool2d_vec_kernel<T, KH_, KW_, SH_, SW_, PW_, true, 8>),   \
+                                       dim3(unsigned(pgrid)), dim3(256), lds, s, v);               \
+        else hipLaunchKernelGGL((pool2d_vec_kernel<T, KH_, KW_, SH_, SW_, PW_, false, 8>),         \
+                                dim3(unsigned(pgrid)), dim3(256), lds, s, v);                      \
+      }                                                                                            \
+      return hipGetLastError();                                                                    \
+    }                                                                                              \
+  }
+  GS_POOL_VEC(3, 3, 2, 2, 1)
+  GS_POOL_VEC(2, 2, 2, 2, 0)
+  GS_POOL_VEC(3, 3, 1, 1, 1)
+#undef GS_POOL_VEC
+  const unsigned grid = unsigned(a.tasks < (1 << 22) ? a.tasks : (1 << 22));
+  hipLaunchKernelGGL((pool2d_kernel<T>), dim3(grid), dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_windows_reduce_any(const WindowsReduceArgs& a, hipStream_t s) {
+  const hipError_t e = launch_pool2d_t<T>(a, s);
+  if (e != hipErrorInvalidValue) return e;
+  return launch_windows_reduce_t<T>(a, s);
+}
+
 hipError_t launch_windows_reduce(const WindowsReduceArgs& a, hipStream_t s) {
   switch (a.in_dtype) {
-    case GS_I8: return launch_windows_reduce_t<int8_t>(a, s);
-    case GS_I32: return launch_windows_reduce_t<int32_t>(a, s);
-    case GS_BF16: return launch_windows_reduce_t<uint16_t>(a, s);
-    case GS_F32: return launch_windows_reduce_t<float>(a, s);
+    case GS_I8: return launch_windows_reduce_any<int8_t>(a, s);
+    case GS_I32: return launch_windows_reduce_any<int32_t>(a, s);
+    case GS_BF16: return launch_windows_reduce_any<uint16_t>(a, s);
+    case GS_F32: return launch_windows_reduce_any<float>(a, s);
     default: return hipErrorInvalidValue;
   }
 }

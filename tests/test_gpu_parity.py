@@ -56,6 +56,14 @@ WINDOW_CASES = [
     ("bf16", (3, 16, 20, 20), 1, (16, 3, 3), (1, 1, 1), (0, 1, 1), (0, 1, 1), gs.GS_PAD_ZERO),
     ("i32", (2, 2, 6, 7), 2, (2, 2), (2, 2), None, None, gs.GS_PAD_LOWEST),
     ("bf16", (2, 3, 15, 15), 1, (3, 7, 7), (1, 2, 2), (0, 3, 3), (0, 3, 3), gs.GS_PAD_ZERO),
+    # convolution-shaped windows through LDS: 16-byte rows, several channel passes, strides,
+    # asymmetric padding, every element size
+    ("bf16", (2, 8, 24, 32), 1, (8, 3, 3), (1, 1, 1), (0, 1, 1), (0, 1, 1), gs.GS_PAD_ZERO),
+    ("bf16", (1, 320, 6, 40), 1, (320, 3, 3), (1, 1, 1), (0, 1, 1), (0, 1, 1), gs.GS_PAD_ZERO),
+    ("i8", (2, 48, 10, 48), 1, (48, 3, 3), (1, 2, 2), (0, 1, 1), (0, 1, 1), gs.GS_PAD_LOWEST),
+    ("i8", (1, 16, 9, 21), 1, (16, 2, 4), (1, 1, 3), (0, 0, 2), (0, 1, 0), gs.GS_PAD_ZERO),
+    ("f32", (3, 4, 11, 12), 1, (4, 5, 3), (1, 2, 1), (0, 2, 1), (0, 2, 1), gs.GS_PAD_LOWEST),
+    ("i32", (1, 8, 7, 9), 1, (8, 1, 1), (1, 2, 2), None, None, gs.GS_PAD_ZERO),
 ]
 
 
@@ -244,6 +252,11 @@ POOL_CASES = [
     ("i8", (1, 4, 9, 12), (3, 2), (1, 2), (1, 0)),
     ("f32", (2, 2, 8, 8), (8, 8), (1, 1), None),
     ("i32", (3, 3, 10, 10), (2, 2), (2, 2), None),
+    ("bf16", (3, 4, 112, 112), (3, 3), (2, 2), (1, 1)),     # the ResNet stem pooling plane
+    ("bf16", (1, 2, 150, 136), (3, 3), (2, 2), (1, 1)),     # several bands of rows per plane
+    ("f32", (1, 3, 70, 200), (5, 3), (3, 2), (2, 1)),       # run-time window, several bands
+    ("i8", (2, 3, 33, 64), (2, 2), (2, 2), None),
+    ("i8", (1, 2, 31, 35), (3, 3), (1, 1), (1, 1)),
 ]
 
 
@@ -266,6 +279,30 @@ def test_sum_pool_and_1d_windows_reduce():
     node = ap.windows(ap.access(ap.pad(ap.tensor(to_oracle(x)), 1, 2, 2, 0.0), 1), (5,), (3,))
     want = ap.compute(ap.scale(0.2), ap.compute(ap.reduceSum, node)).materialize()
     assert_parity(got, want, float_tol=1e-5)
+
+
+SUM_POOL_CASES = [
+    ("bf16", (2, 6, 7, 7), (7, 7), (1, 1), None, 1.0 / 49.0, torch.float32),
+    ("bf16", (2, 3, 40, 48), (3, 3), (2, 2), (1, 1), 1.0 / 9.0, torch.bfloat16),
+    ("i8", (2, 3, 12, 16), (2, 2), (2, 2), None, 1.0, torch.int32),
+    ("f32", (1, 2, 90, 100), (4, 4), (4, 4), None, 0.0625, torch.float32),
+]
+
+
+@pytest.mark.parametrize("case", SUM_POOL_CASES)
+def test_sum_pool_2d(case):
+    dtype, shape, window, stride, pad, scale, odt = case
+    x = gen(dtype, shape, 1960 + shape[-1])
+    got = gs.windows_reduce(x.to(DEV), 2, window, stride, pad, pad, gs.GS_SUM, scale=scale, out_dtype=odt)
+    node = ap.tensor(to_oracle(x))
+    if pad:
+        node = ap.pad(ap.pad(node, 2, pad[0], pad[0], 0), 3, pad[1], pad[1], 0)
+    prog = ap.compute(ap.reduceSum, ap.windows(ap.access(node, 2), window, stride))
+    if scale != 1.0:
+        prog = ap.compute(ap.scale(scale), prog)
+    # fp32 accumulation of up to 49 terms against an fp64 sum: error <= 49 * 2^-24 * sum|x|, and the
+    # result may be 1e-3 of that sum after cancellation (the floor in rel_error) -> 1e-4 covers it.
+    assert_parity(got, prog.materialize(), float_tol=1e-2 if odt == torch.bfloat16 else 1e-4)
 
 
 @pytest.mark.parametrize("dtype", ["i32", "bf16", "f32"])
