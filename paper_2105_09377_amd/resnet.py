@@ -1,0 +1,85 @@
+"""ResNet-18-shaped convolution stack as a fixed sequence of library calls.
+
+Every layer is one access-pattern program of the paper evaluated by the HIP library:
+
+* convolutions are Fig. 2a (`conv2d_direct_packed`, windows formed on chip) -- except the stem,
+  whose 3 input channels are below the direct kernel's channel step and which therefore runs as
+  the im2col-rewritten form of Fig. 5 (`conv2d_im2col`);
+* ReLU and the residual addition (the `reduceSum (pair a b)` idiom of Sec. 5.4) are fused into the
+  convolution epilogues;
+* max pooling is Fig. 2c (`windows_reduce`), the global average is `compute reduceSum` with a
+  scale (`reduce`), the classifier is `compute dotProd (cartProd ...)` (`cartesian_dot`).
+
+This module only sequences calls and owns the buffers; it does no arithmetic.  No batch-norm and
+no biases: the stack exercises the operators the paper defines, with the layer shapes of the network.
+"""
+
+from __future__ import annotations
+
+from typing import Dict, List, Tuple
+
+import torch
+
+from . import binding as gs
+from .synth import RESNET18_CONVS
+
+
+class ResNet18Stack:
+    def __init__(self, weights: Dict[str, torch.Tensor], batch: int, image: int, device="cuda:0"):
+        self.dev = torch.device(device)
+        self.batch, self.image = batch, image
+        self.w = {k: v.to(self.dev) for k, v in weights.items()}
+        self.spec = {name: (cin, cout, k, s, p) for name, cin, cout, k, s, p in RESNET18_CONVS}
+        # Weights are constants: pack them once, in the order the contraction reads them.
+        self.packed = {name: gs.conv2d_pack_weights(self.w[name]) for name in self.spec if name != "conv1"}
+        self.bufs: Dict[str, torch.Tensor] = {}
+        self.x = torch.empty((batch, 3, image, image), dtype=torch.bfloat16, device=self.dev)
+        h = self._out(image, 7, 2, 3)
+        self._alloc("conv1", (batch, 64, h, h))
+        ws = gs.conv2d_workspace(self.x, self.w["conv1"], (2, 2), (3, 3), form="im2col")
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
+        h = self._out(h, 3, 2, 1)
+        self._alloc("pool", (batch, 64, h, h))
+        for name, (cin, cout, k, s, p) in self.spec.items():
+            if name == "conv1":
+                continue
+            if name.endswith("c1"):
+                hin = h
+                h = self._out(h, k, s, p)
+            elif name.endswith("proj"):
+                assert self._out(hin, k, s, p) == h
+            self._alloc(name, (batch, cout, h, h))
+        self._alloc("avg", (batch, 512))
+        self.logits = torch.empty((batch, self.w["fc"].shape[0]), dtype=torch.float32, device=self.dev)
+
+    @staticmethod
+    def _out(h: int, k: int, s: int, p: int) -> int:
+        return (h + 2 * p - k) // s + 1
+
+    def _alloc(self, name: str, shape: Tuple[int, ...]) -> None:
+        self.bufs[name] = torch.empty(shape, dtype=torch.bfloat16, device=self.dev)
+
+    def _conv(self, name: str, x: torch.Tensor, residual=None, relu=True) -> torch.Tensor:
+        _cin, _cout, k, s, p = self.spec[name]
+        return gs.conv2d_direct_packed(x, self.w[name], self.packed[name], (s, s), (p, p), residual=residual,
+                                       act=gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE, out=self.bufs[name])
+
+    def layer_calls(self) -> List[str]:
+        """Names of the library calls of one forward pass, in order."""
+        return ["conv1", "pool"] + [n for n in self.spec if n != "conv1"] + ["avg", "fc"]
+
+    def forward(self, x: torch.Tensor = None) -> torch.Tensor:
+        if x is not None:
+            self.x.copy_(x)
+        y = gs.conv2d_im2col(self.x, self.w["conv1"], (2, 2), (3, 3), act=gs.GS_ACT_RELU,
+                             out=self.bufs["conv1"], workspace=self.ws)
+        y = gs.windows_reduce(y, 2, (3, 3), (2, 2), (1, 1), (1, 1), gs.GS_MAX, out=self.bufs["pool"])
+        for stage in (1, 2, 3, 4):
+            for block in (1, 2):
+                pre = f"s{stage}b{block}"
+                t = self._conv(pre + "c1", y)
+                shortcut = self._conv(pre + "proj", y, relu=False) if (pre + "proj") in self.spec else y
+                y = self._conv(pre + "c2", t, residual=shortcut)
+        hw = y.shape[-1] * y.shape[-2]
+        avg = gs.reduce(y, 2, gs.GS_SUM, scale=1.0 / hw, out=self.bufs["avg"])
+        return gs.cartesian_dot(avg, self.w["fc"], out=self.logits)
