@@ -2,6 +2,9 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18|conv3x3]
 
+The default workload is the ResNet-18-shaped stack at batch 64, the largest of the five
+configurations and the only one that passes through every step of the hot path.
+
 A step is one pass of the workload's whole call sequence over one batch of synthetic input that
 is already resident in HBM.  Steps are captured once into HIP graphs (one per rotating buffer
 set, so that consecutive steps do not find their inputs in cache) and replayed; the timed region
@@ -26,6 +29,30 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 ROTATE_BYTES = 512 << 20      # rotate over enough buffer sets to exceed the last-level cache
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each
+# scaled by the same counter's reading for a plain copy of known size; see profiles/).  A reading
+# only counts for the kernel sources it was taken with: their hash is stored beside it and the
+# bench reports null once the sources differ.
+KERNEL_SOURCES = ("conv_kernels.h", "conv3_inst.hip", "conv.hip", "common.h")
+TRAFFIC = {
+    "resnet18": {"bytes": 60.18e6 + 25.69e6, "sources": "1d7194cd32eaba2d276c8d27464cdc95e7e26341c9c8ec615bea1e0d12463026"},
+    "conv3x3": {"bytes": 24.68e6 + 12.85e6, "sources": None},
+}
+
+
+def _sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2105_09377_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def _traffic(workload):
+    t = TRAFFIC.get(workload)
+    return t["bytes"] if t and t["sources"] == _sources_digest() else None
+
 
 def _graph_of(fn, stream):
     """Capture fn() (already warmed up) into a HIP graph on `stream`."""
@@ -47,6 +74,13 @@ def _time_region(launchers, steps, stream):
         stop.record(stream)
     torch.cuda.synchronize()
     return time.perf_counter() - t0, start.elapsed_time(stop)
+
+
+def _bf16_to_f64(t):
+    """Exact float64 values of a CPU bfloat16 tensor (for the CPU baseline's oracle)."""
+    import numpy as np
+    from oracle import numerics
+    return numerics.bf16_bits_to_f64(t.contiguous().view(torch.int16).numpy().view(np.uint16))
 
 
 class Conv3x3:
@@ -95,15 +129,70 @@ class Conv3x3:
                 "kind": "oracle", "sample": f"brute-force C loops (fp64, OpenMP) on all {n} images of the workload, {dt:.2f} s"}
 
 
-WORKLOADS = {"conv3x3": Conv3x3}
+class ResNet18:
+    """ResNet-18-shaped stack forward at batch 64 (the largest of the five workloads): stem
+    convolution as im2col + dense contraction, max pooling, sixteen 3x3 and three 1x1 convolutions
+    with fused residual / ReLU, global average, classifier."""
+
+    name = "resnet18-shaped conv stack forward, batch 64, 3x224x224, bf16 in/out, fp32 accumulate"
+    dominant = "conv_direct3_kernel (stage 1: N=64 C=64 56x56 -> 64, 3x3 s1 p1; 4 of the 20 convolutions)"
+
+    def __init__(self, dev):
+        from paper_2105_09377_amd import binding as gs, synth
+        from paper_2105_09377_amd.resnet import ResNet18Stack
+        self.gs = gs
+        self.cfg = synth.resnet18_stack(batch=64, image=224)
+        self.nsets = 2                       # one step touches > 600 MB: two sets defeat every cache
+        self.nets = [ResNet18Stack(self.cfg["weights"], 64, 224, dev) for _ in range(self.nsets)]
+        for net in self.nets:
+            net.x.copy_(self.cfg["x"])
+        hw, flops = 224, 0.0
+        for name, cin, cout, k, s, p in synth.RESNET18_CONVS:
+            if name == "conv1":
+                hin = hw
+                hw = (hw + 2 * p - k) // s + 1
+                out_hw = hw
+                hw = (hw + 2 - 3) // 2 + 1          # max pooling
+            elif name.endswith("c1"):
+                hin = hw
+                hw = (hw + 2 * p - k) // s + 1
+                out_hw = hw
+            else:
+                out_hw = hw
+            flops += 2.0 * 64 * out_hw * out_hw * cout * cin * k * k
+        flops += 2.0 * 64 * 512 * 1000
+        self.flops = flops
+        self.dominant_flops = 2.0 * 64 * 56 * 56 * 64 * 64 * 9
+
+    def step(self, i):
+        self.nets[i].forward()
+
+    def dominant_launch(self, i):
+        net = self.nets[i]
+        net._conv("s1b1c1", net.bufs["pool"])
+
+    def cpu_baseline(self):
+        from oracle import brute, resnet as oresnet
+        from paper_2105_09377_amd import synth
+        n = 64
+        x = _bf16_to_f64(self.cfg["x"][:n])
+        w = {k: _bf16_to_f64(v) for k, v in self.cfg["weights"].items()}
+        t0 = time.perf_counter()
+        oresnet.forward(x, w, synth.RESNET18_CONVS)
+        dt = time.perf_counter() - t0
+        return {"value": self.flops * n / 64 / dt / 1e12, "unit": "TFLOP/s", "cores": brute.num_threads(),
+                "kind": "oracle", "sample": f"the stack oracle (fp64 C loops, OpenMP) on {n} of the 64 images, {dt:.1f} s"}
+
+
+WORKLOADS = {"conv3x3": Conv3x3, "resnet18": ResNet18}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="conv3x3", choices=sorted(WORKLOADS))
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="resnet18", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB -> 256 MiB elementwise copy 10 times and exit (reference "
@@ -159,7 +248,7 @@ def main():
         "event_ms_per_step": ev_ms / args.steps,
         "roofline": {"bound": "mfma", "kernel": wl.dominant, "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "us_per_launch": dom_s * 1e6, "traffic": None},
+                     "us_per_launch": dom_s * 1e6, "traffic": _traffic(args.workload)},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = wl.cpu_baseline()
