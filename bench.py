@@ -135,7 +135,7 @@ class ResNet18:
     with fused residual / ReLU, global average, classifier."""
 
     name = "resnet18-shaped conv stack forward, batch 64, 3x224x224, bf16 in/out, fp32 accumulate"
-    dominant = "conv_direct3_kernel (stage 1: N=64 C=64 56x56 -> 64, 3x3 s1 p1; 4 of the 20 convolutions)"
+    dominant = "conv_direct4_kernel (stage 1: N=64 C=64 56x56 -> 64, 3x3 s1 p1; 4 of the 20 convolutions)"
 
     def __init__(self, dev):
         from paper_2105_09377_amd import binding as gs, synth

@@ -1,7 +1,7 @@
 // One translation unit per (element type, tile shape) of the pipelined convolution kernel, so
 // that the many template instances compile in parallel.  Built several times with different
 // -DGS_CONV3_TRAITS / -DGS_CONV3_TILE / -DGS_CONV3_NAME (see build.py).
-#include "conv_kernels.h"
+#include "conv4_kernel.h"
 
 namespace gs {
 
@@ -33,6 +33,49 @@ static hipError_t launch_conv3_cfg(const ConvArgs& a, ConvGeom g, hipStream_t s)
   return hipGetLastError();
 }
 
+// Producer / consumer kernel (eight waves): returns hipErrorInvalidValue when the shape does not
+// fit it.  Three weight buffers when the output-channel tile is 64 wide, two when it is 128.
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI>
+static hipError_t launch_conv4_cfg(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes, hipStream_t s) {
+  constexpr int NWB = TO <= 64 ? 3 : 2;
+  auto kern = conv_direct4_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, NWB>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int64_t tiles = ceil_div(g.M, TP) * ceil_div(a.O, TO);
+  const int64_t grid = tiles < conv_num_cus() ? tiles : conv_num_cus();
+  hipLaunchKernelGGL(kern, dim3(unsigned(grid)), dim3(512), lds_bytes, s, a, g);
+  return hipGetLastError();
+}
+
+// Picks the pixel-vector width: a producer thread moves one item of VW pixels x 8 (16) channels
+// per chunk, so the narrowest vector whose items still fit one (then two) per thread keeps the
+// most producer lanes busy.
+template <typename TR, int TO, int TP, int WO, int WP, int KH, int KW>
+static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
+  constexpr int NWB = TO <= 64 ? 3 : 2;
+  const int nchunk = a.Cpad / (32 / TR::kEsz);
+  if (nchunk % 4 != 0) return hipErrorInvalidValue;   // the ring holds four chunks
+  g.max_rows = conv_max_rows(a, g.M, g.HWo, TP);
+  if (g.max_rows < 0) return hipErrorInvalidValue;
+  const size_t stage_bytes = 4 * 32 * size_t(TP / WP * 4 + 16);   // epilogue staging, one region per wave
+  const size_t patch_bytes = 2 * size_t(g.max_rows) * g.PW * 48;
+  const size_t lds_bytes = 1024 + NWB * size_t(a.Kh * a.Kw) * TO * 32 + patch_bytes + stage_bytes;
+  if (lds_bytes > size_t(kLdsLimit)) return hipErrorInvalidValue;
+  auto items = [&](int vw) { return int64_t(g.max_rows) * (a.W / vw) * 2; };
+#define GS_TRY(VW_, MAXI_)                                                                   \
+  if (a.W % VW_ == 0 && items(VW_) <= 256 * MAXI_)                                          \
+    return launch_conv4_cfg<TR, TO, TP, WO, WP, VW_, KH, KW, MAXI_>(a, g, lds_bytes, s);
+  GS_TRY(1, 1) GS_TRY(2, 1) GS_TRY(4, 1) GS_TRY(8, 1)
+  GS_TRY(1, 2) GS_TRY(2, 2) GS_TRY(4, 2)   // (8, 2) would need 256 ring registers
+#undef GS_TRY
+  return hipErrorInvalidValue;
+}
+
 template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW>
 static hipError_t launch_conv3_depth(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
   const int nchunk = a.Cpad / (32 / TR::kEsz);
@@ -50,6 +93,11 @@ static hipError_t launch_conv3_taps(const ConvArgs& a, const ConvGeom& g, hipStr
 template <typename TR, int TO, int TP, int WO, int WP>
 static hipError_t launch_conv3_vw(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
   constexpr int ESZ = TR::kEsz;
+  {
+    const hipError_t e = (a.Kh == 3 && a.Kw == 3) ? launch_conv4<TR, TO, TP, WO, WP, 3, 3>(a, g, s)
+                                                  : launch_conv4<TR, TO, TP, WO, WP, 0, 0>(a, g, s);
+    if (e != hipErrorInvalidValue) return e;
+  }
   // Widest pixel vector whose loads stay aligned: W (hence every row start) a multiple of it.
   if (a.W % 8 == 0) return launch_conv3_taps<TR, TO, TP, WO, WP, 8>(a, g, s);
   if (a.W % 4 == 0) return launch_conv3_taps<TR, TO, TP, WO, WP, 4>(a, g, s);

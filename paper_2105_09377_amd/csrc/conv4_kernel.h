@@ -1,0 +1,558 @@
+// Producer / consumer form of the direct convolution (Fig. 2a with the windows formed on chip).
+//
+// Same tiling and LDS layout as conv_direct3_kernel (conv_kernels.h), but a workgroup has eight
+// waves, two per SIMD, with fixed roles:
+//   * waves 0-3, the consumers, only read MFMA fragments from LDS, multiply, and write results;
+//   * waves 4-7, the producers, only move data: activation rows global -> registers (a ring two
+//     chunks deep) -> transposed 16-byte LDS writes, and weight slabs global -> LDS directly.
+// A SIMD therefore always has a wave with MFMAs to issue next to a wave doing address, packing
+// and memory work, and the hardware interleaves them; with four do-everything waves those phases
+// ran one after the other.  One workgroup barrier per channel chunk hands a filled patch / weight
+// buffer from the producers to the consumers and a drained one back.  The producers run through
+// tile boundaries without a gap (chunk 0 of the next tile is stored during the last chunk of this
+// one), so the consumers' epilogue overlaps the producers' work for the next tile; the epilogue
+// stages results in an LDS region of its own for that reason.
+#pragma once
+#include "conv_kernels.h"
+
+#include <limits.h>
+
+namespace gs {
+
+// Row segments of a tile of positions [m0, mend), computed on the fly (no table): the tile touches
+// images n_first .. n_first + nseg - 1; segment s holds the input rows ihlo .. ihlo + rows - 1 of
+// its image, stored in the patch from row `base` on.
+struct TileSegs {
+  int m0, mend, n_first, nseg;
+};
+__device__ __forceinline__ TileSegs tile_segs(int m0, int mend, const ConvGeom& g) {
+  TileSegs t;
+  t.m0 = m0;
+  t.mend = mend;
+  t.n_first = int(g.dHWo.div(uint32_t(m0)));
+  t.nseg = int(g.dHWo.div(uint32_t(mend - 1))) - t.n_first + 1;
+  return t;
+}
+__device__ __forceinline__ void seg_extent(const TileSegs& t, int s, const ConvGeom& g, int Sh, int Ph,
+                                           int Kh, int* ihlo, int* rows) {
+  const int img0 = (t.n_first + s) * g.HWo;
+  const int pa = (t.m0 > img0 ? t.m0 : img0) - img0;
+  const int e = t.mend < img0 + g.HWo ? t.mend : img0 + g.HWo;
+  const int pb = e - 1 - img0;
+  const int ho_a = int(g.dWo.div(uint32_t(pa))), ho_b = int(g.dWo.div(uint32_t(pb)));
+  *ihlo = ho_a * Sh - Ph;
+  *rows = (ho_b - ho_a) * Sh + Kh;
+}
+// Patch row r -> (segment, input row); returns false past the last row.
+__device__ __forceinline__ bool seg_of_row(const TileSegs& t, int r, const ConvGeom& g, int Sh, int Ph,
+                                           int Kh, int* seg, int* ih) {
+  int base = 0;
+  for (int s = 0; s < t.nseg; ++s) {
+    int ihlo, rows;
+    seg_extent(t, s, g, Sh, Ph, Kh, &ihlo, &rows);
+    if (r < base + rows) {
+      *seg = s;
+      *ih = ihlo + (r - base);
+      return true;
+    }
+    base += rows;
+  }
+  return false;
+}
+
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int NWB>
+__global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom g) {
+  static_assert(WO * WP == 4, "four consumer waves");
+  static_assert(NWB == 2 || NWB == 3, "weight buffers");
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  constexpr int D = 4;                   // ring depth: chunks of patch loads in flight per thread
+  constexpr int ESZ = TR::kEsz;
+  constexpr int G = 16 / ESZ;            // channels per 16-byte vector
+  constexpr int CCH = 32 / ESZ;          // channels per chunk
+  constexpr int PIXB = 48;               // LDS bytes per patch pixel: 32 + 16 pad (odd multiple of 16)
+  constexpr int WOT = TO / WO, WPT = TP / WP;
+  constexpr int MI = WOT / 32, NJ = WPT / 32;
+  constexpr int OB = TO / 32;            // 32-row weight blocks per tap
+  constexpr int LB = VW * ESZ;           // bytes per patch load
+  constexpr int RS = WPT * 4 + 16;       // epilogue staging row stride in bytes
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  // The role must be a scalar (wave-uniform) value: a wave that ran the other role's code with
+  // all lanes masked off would still arrive at its barriers.
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool producer = wave >= 4;
+  const int M = int(g.M);
+  const int tiles_m = (M + TP - 1) / TP;
+  const int n_tiles = tiles_m * ((a.O + TO - 1) / TO);
+  const FastDiv dTiles = FastDiv::make(uint32_t(tiles_m));
+  const int Kh = KH ? KH : a.Kh, Kw = KW ? KW : a.Kw;
+  const int T = Kh * Kw;
+  const int nchunk = a.Cpad / CCH;       // a multiple of D (checked by the host)
+
+  const int wbytes = T * TO * 32;                     // one weight buffer
+  const int pbytes = g.max_rows * g.PW * PIXB;        // one patch buffer
+  uint8_t* wl = lds + 1024;                           // [NWB][wbytes], 1 KB aligned; dummy area at lds + 512
+  uint8_t* pl = wl + NWB * wbytes;                    // [2][pbytes]
+  uint8_t* sl = pl + 2 * pbytes;                      // [4][32 * RS] epilogue staging
+
+  auto tile_range = [&](int tile, int* m0, int* mend, int* o0) {
+    const int to = int(dTiles.div(uint32_t(tile)));
+    *m0 = (tile - to * tiles_m) * TP;
+    *o0 = to * TO;
+    *mend = *m0 + TP < M ? *m0 + TP : M;
+  };
+
+  int tile = blockIdx.x;
+  if (tile >= n_tiles) return;
+  {  // patch buffers start as zeros: the halo columns are never written again
+    const i32x4 z = {0, 0, 0, 0};
+    for (int off = tid * 16; off < 2 * pbytes; off += 512 * 16) *reinterpret_cast<i32x4*>(pl + off) = z;
+  }
+  __syncthreads();
+
+  if (producer) {
+    // =========================================================================================
+    // Producers.  Three cursors walk the same sequence of (tile, chunk) units, each a fixed
+    // distance ahead of the consumers: stores 1 unit, weight transfers NWB - 1 units, patch loads
+    // 1 + D units.  Crossing into the next tile only means rebuilding that cursor's descriptors.
+    // =========================================================================================
+    const int ptid = tid - 256, pwave = wave - 4;
+    const uint8_t* act = static_cast<const uint8_t*>(a.act);
+    const uint8_t* wr = static_cast<const uint8_t*>(a.wr);
+    const int64_t plane = int64_t(a.H) * a.W * ESZ;     // bytes per channel plane
+    const int64_t wr_row = int64_t(T) * a.Cpad * ESZ;   // bytes per output channel in wr
+    const int XGn = a.W / VW;                           // pixel groups per row
+    const FastDiv dXG = FastDiv::make(uint32_t(XGn));
+    const FastDiv dPW = FastDiv::make(uint32_t(g.PW));
+    const int n_wq = T * OB;
+
+    struct Cursor {
+      int tile, chunk;
+    };
+    struct Items {
+      const uint8_t* src[MAXI];
+      int dst[MAXI];
+      uint32_t okbits;          // bit i: item i exists
+    };
+    auto make_items = [&](int tile_, Items& it) {
+      int m0_, mend_, o0_;
+      tile_range(tile_, &m0_, &mend_, &o0_);
+      const TileSegs ts = tile_segs(m0_, mend_, g);
+      it.okbits = 0;
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        const int id = ptid + 256 * i;
+        it.src[i] = act;
+        it.dst[i] = 512;          // dummy area (VW * 48 bytes at most)
+        const int rc = int(dXG.div(uint32_t(id))), xg = id - rc * XGn;
+        const int cg = rc & 1, r = rc >> 1;
+        int s, ih;
+        if (seg_of_row(ts, r, g, a.Sh, a.Ph, a.Kh, &s, &ih) && ih >= 0 && ih < a.H) {
+          it.okbits |= 1u << i;
+          it.src[i] = act + (int64_t(ts.n_first + s) * a.C + cg * G) * plane +
+                      (int64_t(ih) * a.W + xg * VW) * ESZ;
+          it.dst[i] = int(pl - lds) + (r * g.PW + g.XO + xg * VW) * PIXB + cg * 16;
+        }
+      }
+    };
+    // Rows of a tile's patch that lie outside their image (top / bottom padding) must read as
+    // zeros; a row index may have held data of the previous tile, so they are cleared per tile
+    // and buffer.  Data rows are overwritten in full and need no clearing.
+    auto zero_invalid_rows = [&](int tile_, int buf) {
+      int m0_, mend_, o0_;
+      tile_range(tile_, &m0_, &mend_, &o0_);
+      const TileSegs ts = tile_segs(m0_, mend_, g);
+      bool any = false;                                   // uniform: most tiles have none
+      for (int s_ = 0; s_ < ts.nseg; ++s_) {
+        int ihlo, rows;
+        seg_extent(ts, s_, g, a.Sh, a.Ph, a.Kh, &ihlo, &rows);
+        any = any || ihlo < 0 || ihlo + rows > a.H;
+      }
+      if (!any) return;
+      const i32x4 z = {0, 0, 0, 0};
+      for (int id = ptid; id < g.max_rows * g.PW; id += 256) {
+        const int r = int(dPW.div(uint32_t(id)));
+        int s, ih;
+        if (seg_of_row(ts, r, g, a.Sh, a.Ph, a.Kh, &s, &ih) && (ih < 0 || ih >= a.H)) {
+          uint8_t* p = pl + buf * pbytes + id * PIXB;
+          *reinterpret_cast<i32x4*>(p) = z;
+          *reinterpret_cast<i32x4*>(p + 16) = z;
+        }
+      }
+    };
+    // Weight DMA sources of this lane for output-channel tile o0: instruction q covers tap
+    // q / OB, rows (q % OB) * 32 .. + 31; lane i fills (row i / 2, position i % 2).
+    const int wrow = lane >> 1;
+    const int wcol = ((lane & 1) ^ (((wrow >> 2) ^ (wrow >> 3)) & 1)) * 16;
+    struct WSrc { const uint8_t* p[OB]; };
+    auto make_wsrc = [&](int tile_, WSrc& w) {
+      int m0_, mend_, o0_;
+      tile_range(tile_, &m0_, &mend_, &o0_);
+#pragma unroll
+      for (int b = 0; b < OB; ++b) {
+        int o = o0_ + b * 32 + wrow;
+        o = o < a.O ? o : a.O - 1;                      // rows past O are never stored
+        w.p[b] = wr + o * wr_row + wcol;
+      }
+    };
+    constexpr int NWI = KH > 0 ? (KH * KW * OB + 3) / 4 : 0;   // weight instructions per wave and chunk
+    // The descriptors are switched by assignment when a cursor enters a tile; selecting between
+    // two structures per use would make the compiler keep them in scratch memory, whose loads
+    // share the counter that tracks the prefetched global loads.
+    WSrc wld;
+    const uint32_t wl_addr = lds_addr_of(wl);
+    auto issue_weights = [&](int chunk, int slot) {
+      const int64_t coff = int64_t(chunk) * CCH * ESZ;
+      auto one = [&](int q) {
+        const int tap = q / OB, b = q % OB;
+        const uint8_t* src = wld.p[0];
+#pragma unroll
+        for (int bb = 1; bb < OB; ++bb) src = (b == bb) ? wld.p[bb] : src;
+        lds_dma16(src + int64_t(tap) * a.Cpad * ESZ + coff, wl_addr + slot * wbytes + q * 1024);
+      };
+      if constexpr (KH > 0) {
+#pragma unroll
+        for (int k = 0; k < NWI; ++k) {
+          const int q = pwave + 4 * k;
+          one(q < n_wq ? q : n_wq - 1);
+        }
+      } else {
+        for (int q = pwave; q < n_wq; q += 4) one(q);
+      }
+    };
+
+    RingReg<LB> preg[D][MAXI][G];
+    Items ld, st;             // items of the tile being loaded and of the tile being stored
+    auto load_patch = [&](int chunk, auto slot_) {
+      constexpr int slot = decltype(slot_)::value;
+      const int64_t coff = int64_t(chunk) * CCH * plane;
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+#pragma unroll
+        for (int t = 0; t < G; ++t) preg[slot][i][t].load(ld.src[i] + coff + t * plane);
+      }
+    };
+    // Items that do not exist read valid dummy addresses and write into a 512-byte dummy area
+    // at lds + 512, so that no branch separates a ring load from its use.
+    auto store_patch = [&](auto slot_, int buf) {
+      constexpr int slot = decltype(slot_)::value;
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        uint8_t* pb = lds + st.dst[i] + (((st.okbits >> i) & 1u) ? buf * pbytes : 0);
+#pragma unroll
+        for (int p = 0; p < VW; ++p) {
+          i32x4 v;   // pixel p: element t = channel t of the group
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 4 / ESZ; ++e) {
+              const int t = d * (4 / ESZ) + e;
+              const int boff = p * ESZ;
+              const uint32_t word = preg[slot][i][t].word(boff / 4);
+              const uint32_t val = (word >> ((boff % 4) * 8)) & (ESZ == 2 ? 0xffffu : 0xffu);
+              w |= val << (e * ESZ * 8);
+            }
+            v[d] = int32_t(w);
+          }
+          *reinterpret_cast<i32x4*>(pb + p * PIXB) = v;
+        }
+      }
+    };
+    // Cursor steps.  Past the last tile a cursor keeps its descriptors: surplus loads and weight
+    // transfers re-read valid addresses and are never consumed; surplus stores are skipped.
+    const int step = int(gridDim.x);
+    auto next_unit = [&](Cursor& c) {
+      bool new_tile = false;
+      if (++c.chunk == nchunk) {
+        c.chunk = 0;
+        c.tile += step;
+        new_tile = c.tile < n_tiles;
+      }
+      return new_tile;
+    };
+    Cursor lc = {tile, 0}, sc = {tile, 0}, wc = {tile, 0};
+
+    // ---- prologue: ring and weight pipeline primed, chunk 0 of the first tile in LDS ----------
+    make_items(tile, ld);
+    st = ld;
+    make_wsrc(tile, wld);
+    static_for<D>([&](auto d_) {
+      load_patch(lc.chunk, d_);
+      if (next_unit(lc)) make_items(lc.tile, ld);
+    });
+    static_for<NWB - 1>([&](auto k_) {
+      issue_weights(wc.chunk, decltype(k_)::value);
+      if (next_unit(wc)) make_wsrc(wc.tile, wld);
+    });
+    store_patch(std::integral_constant<int, 0>{}, 0);     // nothing to clear: the buffers are zero
+    if (next_unit(sc)) make_items(sc.tile, st);
+    load_patch(lc.chunk, std::integral_constant<int, 0>{});
+    if (next_unit(lc)) make_items(lc.tile, ld);
+    wait_vmem<0>();
+    lds_barrier();                                       // B0: chunk 0 of the first tile is ready
+    int wslot = 0;                                       // LDS weight buffer of the current chunk
+    constexpr int RL = MAXI * G;
+    // Vector-memory instructions issued after the weights of the next chunk: with three buffers
+    // those were sent a whole period earlier (ring load, weights, ring load follow them), with
+    // two buffers in this period (only the ring load follows).
+    constexpr int kWaitWeights = KH > 0 ? (NWB == 3 ? 2 * RL + NWI : RL) : 0;
+
+    for (; tile < n_tiles; tile += step) {
+      for (int cb = 0; cb < nchunk; cb += D) {
+        static_for<D>([&](auto d_) {
+          constexpr int d = decltype(d_)::value;      // the consumers multiply chunk cb + d now
+          constexpr int ns = (d + 1) % D;             // ring slot of the unit stored (and refilled)
+          // the unit after it: registers -> LDS
+          if (sc.tile < n_tiles) {
+            if (sc.chunk <= 1) zero_invalid_rows(sc.tile, sc.chunk);   // first use of this buffer by the tile
+            store_patch(std::integral_constant<int, ns>{}, sc.chunk & 1);
+          }
+          if (next_unit(sc)) make_items(sc.tile, st);
+          {
+            const int slot2 = wslot + NWB - 1 >= NWB ? wslot - 1 : wslot + NWB - 1;
+            issue_weights(wc.chunk, slot2);
+            if (next_unit(wc)) make_wsrc(wc.tile, wld);
+          }
+          wslot = wslot + 1 >= NWB ? 0 : wslot + 1;
+          load_patch(lc.chunk, std::integral_constant<int, ns>{});
+          if (next_unit(lc)) make_items(lc.tile, ld);
+          if constexpr (KH > 0) wait_vmem<kWaitWeights>();
+          else wait_vmem<0>();
+          lds_barrier();
+        });
+      }
+    }
+    wait_vmem<0>();
+    return;
+  }
+
+  // ===========================================================================================
+  // Consumers
+  // ===========================================================================================
+  const int wo = wave / WP, wp = wave % WP;
+  // A-fragment address inside a 1 KB weight block: row (lane % 32), column lane / 32, swizzled.
+  const int afrag = (lane & 31) * 32 + (((lane >> 5) ^ ((((lane & 31) >> 2) ^ ((lane & 31) >> 3)) & 1)) << 4) +
+                    wo * (WOT / 32) * 1024;
+  lds_barrier();                                         // B0
+  int wslot = 0;
+  const bool vec_epi = g.HWo % 4 == 0;
+  int m0, mend, o0;
+  for (; tile < n_tiles; tile += gridDim.x) {
+    tile_range(tile, &m0, &mend, &o0);
+    const TileSegs ts = tile_segs(m0, mend, g);
+    // Per-lane window origins in the patch, and output addresses.
+    int pbase[NJ];
+    uint32_t out_base[NJ];
+    bool pos_ok[NJ];
+#pragma unroll
+    for (int n = 0; n < NJ; ++n) {
+      const int m = m0 + wp * WPT + n * 32 + (lane & 31);
+      pos_ok[n] = m < M;
+      pbase[n] = (lane >> 5) * 16;
+      out_base[n] = 0;
+      if (pos_ok[n]) {
+        const int img = int(g.dHWo.div(uint32_t(m))), p = m - img * g.HWo;
+        const int ho = int(g.dWo.div(uint32_t(p))), wo_ = p - ho * a.Wo;
+        int base = 0, ihlo = 0, rows = 0;              // patch rows in front of this image's segment
+        for (int s = 0; s <= img - ts.n_first; ++s) {
+          base += rows;
+          seg_extent(ts, s, g, a.Sh, a.Ph, a.Kh, &ihlo, &rows);
+        }
+        const int row = base + (ho * a.Sh - a.Ph - ihlo);
+        const int col = wo_ * a.Sw - a.Pw + g.XO;
+        pbase[n] += (row * g.PW + col) * PIXB;
+        out_base[n] = uint32_t(img) * uint32_t(a.O) * uint32_t(g.HWo) + uint32_t(p);
+      }
+    }
+    typename TR::accv_t acc[MI][NJ];
+    static_for<MI>([&](auto m_) {
+      static_for<NJ>([&](auto n_) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[decltype(m_)::value][decltype(n_)::value][v] = 0;
+      });
+    });
+
+    // Write-back geometry of this lane (vector epilogue): its group of 4 positions is the same
+    // for every channel row it writes.
+    constexpr int GR = WPT / 4;                      // 4-position groups per row
+    constexpr int ROWS_PER_IT = 64 / GR;
+    constexpr int NIT = 32 / ROWS_PER_IT;            // write-back steps per 32-channel block
+    uint8_t* stage = sl + wave * (32 * RS);
+    const int gq = lane % GR, rsub = lane / GR;
+    const int mm = m0 + wp * WPT + gq * 4;
+    const bool grp_ok = mm < M;
+    const int gimg = int(g.dHWo.div(uint32_t(grp_ok ? mm : 0)));
+    const uint32_t gbase = uint32_t(gimg) * uint32_t(a.O) * uint32_t(g.HWo) + uint32_t(mm - gimg * g.HWo);
+    const bool has_res = a.residual != nullptr;
+    // bfloat16 residual values are requested before the last chunk's MFMAs and land under them;
+    // 32-bit residuals (twice the registers) are requested per block inside the write-back.
+    const bool res_early = has_res && a.out_dtype == GS_BF16;
+    uint2 resv[MI][NIT];
+    auto request_residual = [&]() {
+      static_for<MI>([&](auto m_) {
+        constexpr int m = decltype(m_)::value;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+          const int o = o0 + wo * WOT + m * 32 + it * ROWS_PER_IT + rsub;
+          const uint32_t addr = (grp_ok && o < a.O) ? gbase + uint32_t(o) * uint32_t(g.HWo) : 0u;
+          resv[m][it] = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a.residual) + addr);
+        }
+      });
+    };
+
+    for (int ch = 0; ch < nchunk; ++ch) {
+      const int buf = ch & 1;
+      if (ch == nchunk - 1 && vec_epi && res_early) request_residual();
+      const uint8_t* wb = wl + wslot * wbytes + afrag;
+      const uint8_t* pb = pl + buf * pbytes;
+      if constexpr (KH > 0) {
+        // Static taps: fragments of tap t+1 are requested before the MFMAs of tap t.
+        constexpr int NT = KH * KW;
+        const uint32_t wa = lds_addr_of(wb);
+        const uint32_t pa = lds_addr_of(pb);
+        i32x4 fr[2][MI + NJ];
+        auto request = [&](int tap, int slot) {
+          const int kh = tap / KW, kw = tap - kh * KW;
+          const uint32_t tapoff = uint32_t((kh * g.PW + kw) * PIXB);
+#pragma unroll
+          for (int m = 0; m < MI; ++m) lds_read_pinned(fr[slot][m], wa + (tap * OB + m) * 1024);
+#pragma unroll
+          for (int n = 0; n < NJ; ++n) lds_read_pinned(fr[slot][MI + n], pa + pbase[n] + tapoff);
+        };
+        request(0, 0);
+        static_for<NT>([&](auto t_) {
+          constexpr int t = decltype(t_)::value;
+          constexpr int slot = t % 2;
+          if constexpr (t + 1 < NT) request(t + 1, (t + 1) % 2);
+          constexpr int ahead = t + 1 < NT ? 1 : 0;
+          lds_wait_tied<ahead * (MI + NJ), MI + NJ>(fr[slot]);
+#pragma unroll
+          for (int m = 0; m < MI; ++m)
+#pragma unroll
+            for (int n = 0; n < NJ; ++n)
+              acc[m][n] = TR::mfma(fr[slot][m], fr[slot][MI + n], acc[m][n]);
+        });
+      } else {
+        for (int kh = 0; kh < Kh; ++kh)
+          for (int kw = 0; kw < Kw; ++kw) {
+            const int tap = kh * Kw + kw;
+            const int tapoff = (kh * g.PW + kw) * PIXB;
+            i32x4 af[MI], bf[NJ];
+#pragma unroll
+            for (int m = 0; m < MI; ++m)
+              af[m] = *reinterpret_cast<const i32x4*>(wb + (tap * OB + m) * 1024);
+#pragma unroll
+            for (int n = 0; n < NJ; ++n)
+              bf[n] = *reinterpret_cast<const i32x4*>(pb + pbase[n] + tapoff);
+#pragma unroll
+            for (int m = 0; m < MI; ++m)
+#pragma unroll
+              for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(af[m], bf[n], acc[m][n]);
+          }
+      }
+      wslot = wslot + 1 >= NWB ? 0 : wslot + 1;
+      lds_barrier();
+    }
+
+    // ---- epilogue: out[(img*O + o)*HWo + p] ------------------------------------------------------
+    // Each wave stages one 32-channel block of its results in its LDS region as 32-bit values and
+    // writes it back 4 positions per lane.  All reads of a block are requested before the first
+    // is used, the residual values were requested before the last chunk's MFMAs, and ReLU is a
+    // maximum with a run-time lower bound, so the write-back is straight-line code.
+    if (vec_epi) {
+      const int lo_i = a.relu ? 0 : INT_MIN;
+      auto write_back = [&](auto kind_) {
+        constexpr int kind = decltype(kind_)::value;   // 0: int32, 1: f32, 2: bf16
+        static_for<MI>([&](auto m_) {
+          constexpr int m = decltype(m_)::value;
+          static_for<NJ>([&](auto n_) {
+            constexpr int n = decltype(n_)::value;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+              *reinterpret_cast<typename TR::acc_t*>(stage + r * RS + (n * 32 + (lane & 31)) * 4) = acc[m][n][v];
+            }
+          });
+          i32x4 raw[NIT];
+#pragma unroll
+          for (int it = 0; it < NIT; ++it)
+            raw[it] = *reinterpret_cast<const i32x4*>(stage + (it * ROWS_PER_IT + rsub) * RS + gq * 16);
+          i32x4 res4[kind == 2 ? 1 : NIT];
+          if constexpr (kind != 2) {
+            if (has_res) {
+#pragma unroll
+              for (int it = 0; it < NIT; ++it) {
+                const int o = o0 + wo * WOT + m * 32 + it * ROWS_PER_IT + rsub;
+                const uint32_t addr = (grp_ok && o < a.O) ? gbase + uint32_t(o) * uint32_t(g.HWo) : 0u;
+                res4[it] = *reinterpret_cast<const i32x4*>(static_cast<const int32_t*>(a.residual) + addr);
+              }
+            }
+          }
+#pragma unroll
+          for (int it = 0; it < NIT; ++it) {
+            const int o = o0 + wo * WOT + m * 32 + it * ROWS_PER_IT + rsub;
+            const uint32_t addr = gbase + uint32_t(o) * uint32_t(g.HWo);
+            const bool ok = grp_ok && o < a.O;
+            if constexpr (kind == 0) {
+              i32x4 r4 = raw[it];
+              if (has_res) r4 += res4[it];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) r4[e] = r4[e] > lo_i ? r4[e] : lo_i;
+              if (ok) *reinterpret_cast<i32x4*>(static_cast<int32_t*>(a.out) + addr) = r4;
+            } else {
+              float f[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) f[e] = __int_as_float(raw[it][e]);
+              if constexpr (kind == 1) {
+                if (has_res) {
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) f[e] += __int_as_float(res4[it][e]);
+                }
+                i32x4 w4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w4[e] = __float_as_int(a.relu ? fmaxf(f[e], 0.0f) : f[e]);
+                if (ok) *reinterpret_cast<i32x4*>(static_cast<float*>(a.out) + addr) = w4;
+              } else {
+                if (has_res) {
+                  const uint32_t qx = resv[m][it].x, qy = resv[m][it].y;
+                  f[0] += __uint_as_float(qx << 16); f[1] += __uint_as_float(qx & 0xffff0000u);
+                  f[2] += __uint_as_float(qy << 16); f[3] += __uint_as_float(qy & 0xffff0000u);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) f[e] = a.relu ? fmaxf(f[e], 0.0f) : f[e];
+                uint2 w2;
+                w2.x = pack_bf16x2(f[0], f[1]);
+                w2.y = pack_bf16x2(f[2], f[3]);
+                if (ok) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + addr) = w2;
+              }
+            }
+          }
+        });
+      };
+      if constexpr (__is_same(typename TR::acc_t, int32_t)) {
+        write_back(std::integral_constant<int, 0>{});
+      } else {
+        if (a.out_dtype == GS_BF16) write_back(std::integral_constant<int, 2>{});
+        else write_back(std::integral_constant<int, 1>{});
+      }
+    } else {
+      static_for<NJ>([&](auto n_) {
+        constexpr int n = decltype(n_)::value;
+        static_for<MI>([&](auto m_) {
+          constexpr int m = decltype(m_)::value;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int o = o0 + wo * WOT + m * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (pos_ok[n] && o < a.O)
+              store_result<typename TR::acc_t>(a.out, a.residual, a.out_dtype,
+                                               out_base[n] + uint32_t(o) * uint32_t(g.HWo), acc[m][n][v],
+                                               a.relu);
+          }
+        });
+      });
+    }
+  }
+}
+
+}  // namespace gs
