@@ -114,13 +114,17 @@ int glenside_conv2d_im2col(const gs_ap* activations, const gs_ap* weights, const
  *                    the weight-side layout change that the systolic-array rewrite (Sec. 5.2) makes
  *                    explicit with (transpose ?a1 ...).  Needs glenside_conv2d_direct_workspace bytes.
  *   _direct_packed : the convolution proper, reading weights only from `packed`; `weights` gives
- *                    shape and dtype, its data pointer is not read.
+ *                    shape and dtype, its data pointer is not read.  `packed` needs the bytes that
+ *                    _pack_weights needs; when it has glenside_conv2d_direct_workspace bytes for
+ *                    these activations, the part behind the weights is scratch for splitting the
+ *                    channel sum among workgroups (layers with few output tiles), overwritten
+ *                    by every call.
  * glenside_conv2d_direct(x, w, ..., ws) == _pack_weights(w, ws) then _direct_packed(x, w, ..., ws). */
 int glenside_conv2d_pack_weights(const gs_ap* weights, void* packed, size_t packed_bytes,
                                  void* stream);
 int glenside_conv2d_direct_packed(const gs_ap* activations, const gs_ap* weights,
                                   const int64_t stride[2], const int64_t pad[2],
-                                  const gs_ap* residual, int act, gs_ap* out, const void* packed,
+                                  const gs_ap* residual, int act, gs_ap* out, void* packed,
                                   size_t packed_bytes, void* stream);
 /* Workspace bytes the two forms need; 0 if the arguments are invalid.  Host only. */
 size_t glenside_conv2d_direct_workspace(const gs_ap* activations, const gs_ap* weights,

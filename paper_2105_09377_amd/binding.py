@@ -182,9 +182,12 @@ def _conv(fn_name: str, ws_name: str, x, w, stride, pad, residual, act, out_dtyp
     return out
 
 
-def conv2d_workspace(x: torch.Tensor, w: torch.Tensor, stride, pad, form: str = "direct") -> int:
+def conv2d_workspace(x: torch.Tensor, w: torch.Tensor, stride, pad, form: str = "direct",
+                     x_shape: Optional[Sequence[int]] = None) -> int:
+    """Workspace bytes of a convolution call; `x_shape` sizes it for activations of another shape
+    (and x's dtype) without needing such a tensor."""
     name = "glenside_conv2d_direct_workspace" if form == "direct" else "glenside_conv2d_im2col_workspace"
-    return int(getattr(lib(), name)(ctypes.byref(make_ap(x, 1)), ctypes.byref(make_ap(w, 1)),
+    return int(getattr(lib(), name)(ctypes.byref(make_ap(x, 1, shape=x_shape)), ctypes.byref(make_ap(w, 1)),
                                     _i64(stride), _i64(pad)))
 
 
@@ -195,15 +198,24 @@ def conv2d_direct(x, w, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NON
                  residual, act, out_dtype, out, workspace)
 
 
-def conv2d_pack_weights(w: torch.Tensor, packed: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Weights (O,C,Kh,Kw) -> the packed form `conv2d_direct_packed` reads (a uint8 buffer)."""
+def conv2d_pack_weights(w: torch.Tensor, packed: Optional[torch.Tensor] = None,
+                        for_input: Optional[tuple] = None) -> torch.Tensor:
+    """Weights (O,C,Kh,Kw) -> the packed form `conv2d_direct_packed` reads (a uint8 buffer).
+
+    `for_input` = (x, stride, pad) sizes a new buffer for that call (`conv2d_workspace`), which may
+    include scratch behind the weights; without it the buffer holds the weights only.
+    """
     L = lib()
     wa = make_ap(w, 1)
     if packed is None:
-        fake_x = gs_ap()
-        fake_x.dtype, fake_x.rank, fake_x.n_access = wa.dtype, 4, 1
-        fake_x.shape[0], fake_x.shape[1], fake_x.shape[2], fake_x.shape[3] = 1, w.shape[1], w.shape[2], w.shape[3]
-        need = L.glenside_conv2d_direct_workspace(ctypes.byref(fake_x), ctypes.byref(wa), _i64((1, 1)), _i64((0, 0)))
+        if for_input is not None:
+            x, stride, pad = for_input
+            need = conv2d_workspace(x, w, stride, pad)
+        else:
+            fake_x = gs_ap()
+            fake_x.dtype, fake_x.rank, fake_x.n_access = wa.dtype, 4, 1
+            fake_x.shape[0], fake_x.shape[1], fake_x.shape[2], fake_x.shape[3] = 1, w.shape[1], w.shape[2], w.shape[3]
+            need = L.glenside_conv2d_direct_workspace(ctypes.byref(fake_x), ctypes.byref(wa), _i64((1, 1)), _i64((0, 0)))
         packed = torch.empty(max(int(need), 16), dtype=torch.uint8, device=w.device)
     _check(L.glenside_conv2d_pack_weights(ctypes.byref(wa), packed.data_ptr(), packed.numel(), _stream(w)),
            "conv2d_pack_weights")

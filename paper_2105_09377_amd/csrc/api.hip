@@ -143,7 +143,10 @@ int conv_check_io(const gs_ap* act, const gs_ap* w, const gs_ap* residual, int a
   return GS_OK;
 }
 
-int64_t im2col_ld(int dtype, int64_t K) { return round_up(K, 16 / int64_t(dtype_size(dtype))); }
+// Row stride of the im2col matrix (and of the padded weight matrix): K rounded up to the 128-byte
+// K slab of the dense kernel.  Columns K..ld are zeros in both operands, so the contraction may
+// run over ld columns and take the direct-to-LDS path.
+int64_t im2col_ld(int dtype, int64_t K) { return round_up(K, 128 / int64_t(dtype_size(dtype))); }
 
 }  // namespace
 
@@ -255,7 +258,10 @@ size_t glenside_conv2d_direct_workspace(const gs_ap* act, const gs_ap* w, const 
                                         const int64_t pad[2]) {
   ConvShape cs;
   if (conv_shape(act, w, stride, pad, &cs)) return 0;
-  return round_up(int64_t(conv_weight_workspace(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw)), 256) + 256;
+  const int64_t wbytes = round_up(int64_t(conv_weight_workspace(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw)), 256) + 256;
+  const int ks = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo);
+  const int64_t scratch = ks > 1 ? int64_t(ks) * cs.N * cs.O * cs.Ho * cs.Wo * 4 : 0;
+  return size_t(wbytes + scratch);
 }
 
 size_t glenside_conv2d_im2col_workspace(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
@@ -286,20 +292,27 @@ int glenside_conv2d_pack_weights(const gs_ap* w, void* packed, size_t packed_byt
 
 int glenside_conv2d_direct_packed(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
                                   const int64_t pad[2], const gs_ap* residual, int actfn,
-                                  gs_ap* out, const void* packed, size_t packed_bytes,
+                                  gs_ap* out, void* packed, size_t packed_bytes,
                                   void* stream) {
   ConvShape cs;
   int st = conv_shape(act, w, stride, pad, &cs);
   if (st) return st;
   gs_ap wshape = *w;            // the packed form carries the data; only the shape is used
-  wshape.data = const_cast<void*>(packed);
+  wshape.data = packed;
   st = conv_check_io(act, &wshape, residual, actfn, out, cs);
   if (st) return st;
+  // The packed weights must be there; the scratch behind them (split channel sums) is optional.
+  const size_t wneed = size_t(round_up(int64_t(conv_weight_workspace(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw)), 256)) + 256;
   const size_t need = glenside_conv2d_direct_workspace(act, w, stride, pad);
-  if (!packed || packed_bytes < need || reinterpret_cast<uintptr_t>(packed) % 16)
+  if (!packed || packed_bytes < wneed || reinterpret_cast<uintptr_t>(packed) % 16)
     return GS_ERR_WORKSPACE;
   ConvArgs a;
   memset(&a, 0, sizeof(a));
+  a.ksplit = 1;
+  if (need > wneed && packed_bytes >= need) {
+    a.ksplit = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo);
+    a.partial = static_cast<uint8_t*>(packed) + wneed;
+  }
   a.act = act->data;
   a.wr = packed;
   a.out = out->data;
@@ -395,7 +408,7 @@ int glenside_conv2d_im2col(const gs_ap* act, const gs_ap* w, const int64_t strid
   g.out_dtype = out->dtype;
   g.I = cs.O;
   g.J = M;
-  g.K = K;
+  g.K = ld;   // the pad columns are zeros on both sides
   g.ldx = g.ldy = ld;
   g.jp = int64_t(cs.Ho) * cs.Wo;
   if (g.jp < 1) g.jp = 1;

@@ -213,12 +213,18 @@ struct ConvArgs {
   int N, C, H, W, O, Kh, Kw, Sh, Sw, Ph, Pw, Ho, Wo;
   int Cpad;               // channels per tap in `wr`
   int relu;
+  int ksplit;             // 1, 2 or 4: the channel chunks are divided among ksplit workgroups
+  void* partial;          // ksplit > 1: [ksplit][N*O*Ho*Wo] 32-bit partial sums
 };
 size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw);
 hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int C, int Kh, int Kw,
                               hipStream_t s);
-// Returns hipErrorInvalidValue if no tile configuration fits the LDS for this shape.
+// Returns hipErrorInvalidValue if no tile configuration fits the LDS for this shape.  With
+// a.ksplit > 1 and a.partial set, kernels that support it split the channel sum (Fig. 6's last
+// blocking rule: partial dot products combined by reduceSum over a pair); others ignore it.
 hipError_t launch_conv(const ConvArgs& a, hipStream_t s);
+// Split the channel sum of this shape?  Returns 1, 2 or 4 (host heuristic: few tiles, many chunks).
+int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo);
 
 struct ReduceArgs {       // out[r] = reduce over `cols` contiguous values
   const void* in;

@@ -180,8 +180,37 @@ static hipError_t launch_conv3(const ConvArgs& a, const ConvGeom& g, hipStream_t
   return i8 ? launch_conv3_i8_t2(a, g, s) : launch_conv3_bf16_t2(a, g, s);
 }
 
+// Combines the partial sums of a split channel sum: out = cvt(relu(sum_k partial[k] + residual)).
+template <typename AccT>
+__global__ void __launch_bounds__(256)
+conv_splitk_finish_kernel(const AccT* __restrict__ partial, int ksplit, int64_t total,
+                          const void* __restrict__ residual, void* __restrict__ out, int out_dtype,
+                          int relu) {
+  for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
+       i += int64_t(gridDim.x) * blockDim.x) {
+    AccT v = partial[i];
+    for (int k = 1; k < ksplit; ++k) v += partial[int64_t(k) * total + i];
+    store_result<AccT>(out, residual, out_dtype, i, v, relu);
+  }
+}
+
+int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo) {
+  const int64_t M = int64_t(N) * Ho * Wo;
+  const int64_t tiles = O > 64 ? ceil_div(M, 128) * ceil_div(O, 128) : ceil_div(M, 256) * ceil_div(O, 64);
+  const int nchunk = conv_cpad(in_dtype, C) / (in_dtype == GS_I8 ? 32 : 16);
+  const int cus = 256;
+  if (tiles * 4 <= cus && nchunk % 16 == 0) return 4;
+  if (tiles * 2 <= cus && nchunk % 8 == 0) return 2;
+  return 1;
+}
+
 template <typename TR>
-static hipError_t launch_conv_t(const ConvArgs& a, hipStream_t s) {
+static hipError_t launch_conv_t(const ConvArgs& a_in, hipStream_t s) {
+  ConvArgs a = a_in;
+  if (a.ksplit < 2 || !a.partial) {
+    a.ksplit = 1;
+    a.partial = nullptr;
+  }
   ConvGeom g;
   g.T = a.Kh * a.Kw;
   g.XO = int(round_up(a.Pw, 2));
@@ -194,6 +223,21 @@ static hipError_t launch_conv_t(const ConvArgs& a, hipStream_t s) {
   g.dWo = FastDiv::make(uint32_t(a.Wo > 0 ? a.Wo : 1));
   if (g.M == 0 || a.O == 0) return hipSuccess;
   hipError_t e = launch_conv3<TR>(a, g, s);
+  if (a.ksplit > 1) {
+    if (e == hipSuccess) {
+      using AccT = typename TR::acc_t;
+      const int64_t total = g.M * a.O;
+      const int64_t b = ceil_div(total, 256);
+      hipLaunchKernelGGL((conv_splitk_finish_kernel<AccT>), dim3(unsigned(b < 4096 ? b : 4096)), dim3(256), 0,
+                         s, static_cast<const AccT*>(a.partial), a.ksplit, total, a.residual, a.out,
+                         a.out_dtype, a.relu);
+      return hipGetLastError();
+    }
+    if (e != hipErrorInvalidValue) return e;
+    a.ksplit = 1;                      // no splitting kernel takes this shape: plain path
+    a.partial = nullptr;
+    e = launch_conv3<TR>(a, g, s);
+  }
   if (e != hipErrorInvalidValue) return e;
   if (a.O > 64) {
     e = launch_conv_tile<TR, 128, 128, 2, 2>(a, g, s);

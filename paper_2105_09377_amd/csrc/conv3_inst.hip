@@ -46,7 +46,7 @@ static hipError_t launch_conv4_cfg(const ConvArgs& a, const ConvGeom& g, size_t 
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  const int64_t tiles = ceil_div(g.M, TP) * ceil_div(a.O, TO);
+  const int64_t tiles = ceil_div(g.M, TP) * ceil_div(a.O, TO) * (a.ksplit > 1 ? a.ksplit : 1);
   const int64_t grid = tiles < conv_num_cus() ? tiles : conv_num_cus();
   hipLaunchKernelGGL(kern, dim3(unsigned(grid)), dim3(512), lds_bytes, s, a, g);
   return hipGetLastError();
@@ -58,8 +58,9 @@ static hipError_t launch_conv4_cfg(const ConvArgs& a, const ConvGeom& g, size_t 
 template <typename TR, int TO, int TP, int WO, int WP, int KH, int KW>
 static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   constexpr int NWB = TO <= 64 ? 3 : 2;
+  const int ksplit = a.ksplit > 1 ? a.ksplit : 1;
   const int nchunk = a.Cpad / (32 / TR::kEsz);
-  if (nchunk % 4 != 0) return hipErrorInvalidValue;   // the ring holds four chunks
+  if (nchunk % (4 * ksplit) != 0) return hipErrorInvalidValue;   // the ring holds four chunks
   g.max_rows = conv_max_rows(a, g.M, g.HWo, TP);
   if (g.max_rows < 0) return hipErrorInvalidValue;
   const size_t stage_bytes = 4 * 32 * size_t(TP / WP * 4 + 16);   // epilogue staging, one region per wave
@@ -98,6 +99,7 @@ static hipError_t launch_conv3_vw(const ConvArgs& a, const ConvGeom& g, hipStrea
                                                   : launch_conv4<TR, TO, TP, WO, WP, 0, 0>(a, g, s);
     if (e != hipErrorInvalidValue) return e;
   }
+  if (a.ksplit > 1) return hipErrorInvalidValue;   // only the kernel above splits the channel sum
   // Widest pixel vector whose loads stay aligned: W (hence every row start) a multiple of it.
   if (a.W % 8 == 0) return launch_conv3_taps<TR, TO, TP, WO, WP, 8>(a, g, s);
   if (a.W % 4 == 0) return launch_conv3_taps<TR, TO, TP, WO, WP, 4>(a, g, s);

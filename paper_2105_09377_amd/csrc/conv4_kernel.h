@@ -83,11 +83,14 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   const bool producer = wave >= 4;
   const int M = int(g.M);
   const int tiles_m = (M + TP - 1) / TP;
-  const int n_tiles = tiles_m * ((a.O + TO - 1) / TO);
+  // A work item ("tile" below) is (position tile, channel tile, K split): the split index runs
+  // fastest so that workgroups launched together share a patch.
+  const int ksplit = a.ksplit, kshift = ksplit == 4 ? 2 : ksplit == 2 ? 1 : 0;
+  const int n_tiles = tiles_m * ((a.O + TO - 1) / TO) * ksplit;
   const FastDiv dTiles = FastDiv::make(uint32_t(tiles_m));
   const int Kh = KH ? KH : a.Kh, Kw = KW ? KW : a.Kw;
   const int T = Kh * Kw;
-  const int nchunk = a.Cpad / CCH;       // a multiple of D (checked by the host)
+  const int nchunk = a.Cpad / CCH / ksplit;   // chunks per work item: a multiple of D (checked by the host)
 
   const int wbytes = T * TO * 32;                     // one weight buffer
   const int pbytes = g.max_rows * g.PW * PIXB;        // one patch buffer
@@ -95,7 +98,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   uint8_t* pl = wl + NWB * wbytes;                    // [2][pbytes]
   uint8_t* sl = pl + 2 * pbytes;                      // [4][32 * RS] epilogue staging
 
-  auto tile_range = [&](int tile, int* m0, int* mend, int* o0) {
+  auto tile_range = [&](int item, int* m0, int* mend, int* o0) {
+    const int tile = item >> kshift;
     const int to = int(dTiles.div(uint32_t(tile)));
     *m0 = (tile - to * tiles_m) * TP;
     *o0 = to * TO;
@@ -201,8 +205,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     // share the counter that tracks the prefetched global loads.
     WSrc wld;
     const uint32_t wl_addr = lds_addr_of(wl);
-    auto issue_weights = [&](int chunk, int slot) {
-      const int64_t coff = int64_t(chunk) * CCH * ESZ;
+    auto issue_weights = [&](int item, int chunk, int slot) {
+      const int64_t coff = int64_t((item & (ksplit - 1)) * nchunk + chunk) * CCH * ESZ;
       auto one = [&](int q) {
         const int tap = q / OB, b = q % OB;
         const uint8_t* src = wld.p[0];
@@ -223,9 +227,10 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
 
     RingReg<LB> preg[D][MAXI][G];
     Items ld, st;             // items of the tile being loaded and of the tile being stored
-    auto load_patch = [&](int chunk, auto slot_) {
+    auto chunk_base = [&](int item) { return (item & (ksplit - 1)) * nchunk; };
+    auto load_patch = [&](int item, int chunk, auto slot_) {
       constexpr int slot = decltype(slot_)::value;
-      const int64_t coff = int64_t(chunk) * CCH * plane;
+      const int64_t coff = int64_t(chunk_base(item) + chunk) * CCH * plane;
 #pragma unroll
       for (int i = 0; i < MAXI; ++i) {
 #pragma unroll
@@ -278,16 +283,16 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     st = ld;
     make_wsrc(tile, wld);
     static_for<D>([&](auto d_) {
-      load_patch(lc.chunk, d_);
+      load_patch(lc.tile, lc.chunk, d_);
       if (next_unit(lc)) make_items(lc.tile, ld);
     });
     static_for<NWB - 1>([&](auto k_) {
-      issue_weights(wc.chunk, decltype(k_)::value);
+      issue_weights(wc.tile, wc.chunk, decltype(k_)::value);
       if (next_unit(wc)) make_wsrc(wc.tile, wld);
     });
     store_patch(std::integral_constant<int, 0>{}, 0);     // nothing to clear: the buffers are zero
     if (next_unit(sc)) make_items(sc.tile, st);
-    load_patch(lc.chunk, std::integral_constant<int, 0>{});
+    load_patch(lc.tile, lc.chunk, std::integral_constant<int, 0>{});
     if (next_unit(lc)) make_items(lc.tile, ld);
     wait_vmem<0>();
     lds_barrier();                                       // B0: chunk 0 of the first tile is ready
@@ -311,11 +316,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           if (next_unit(sc)) make_items(sc.tile, st);
           {
             const int slot2 = wslot + NWB - 1 >= NWB ? wslot - 1 : wslot + NWB - 1;
-            issue_weights(wc.chunk, slot2);
+            issue_weights(wc.tile, wc.chunk, slot2);
             if (next_unit(wc)) make_wsrc(wc.tile, wld);
           }
           wslot = wslot + 1 >= NWB ? 0 : wslot + 1;
-          load_patch(lc.chunk, std::integral_constant<int, ns>{});
+          load_patch(lc.tile, lc.chunk, std::integral_constant<int, ns>{});
           if (next_unit(lc)) make_items(lc.tile, ld);
           if constexpr (KH > 0) wait_vmem<kWaitWeights>();
           else wait_vmem<0>();
@@ -384,10 +389,18 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     const bool grp_ok = mm < M;
     const int gimg = int(g.dHWo.div(uint32_t(grp_ok ? mm : 0)));
     const uint32_t gbase = uint32_t(gimg) * uint32_t(a.O) * uint32_t(g.HWo) + uint32_t(mm - gimg * g.HWo);
-    const bool has_res = a.residual != nullptr;
+    // Destination: the output, or with a split channel sum this split's slice of the partials
+    // (raw 32-bit sums; residual, ReLU and the conversion happen when the slices are combined).
+    const bool split = ksplit > 1;
+    void* const outp = split ? static_cast<void*>(static_cast<int32_t*>(a.partial) +
+                                                   int64_t(tile & (ksplit - 1)) * a.N * a.O * g.HWo)
+                             : a.out;
+    const int odt = split ? (__is_same(typename TR::acc_t, int32_t) ? GS_I32 : GS_F32) : a.out_dtype;
+    const bool relu = !split && a.relu;
+    const bool has_res = !split && a.residual != nullptr;
     // bfloat16 residual values are requested before the last chunk's MFMAs and land under them;
     // 32-bit residuals (twice the registers) are requested per block inside the write-back.
-    const bool res_early = has_res && a.out_dtype == GS_BF16;
+    const bool res_early = has_res && odt == GS_BF16;
     uint2 resv[MI][NIT];
     auto request_residual = [&]() {
       static_for<MI>([&](auto m_) {
@@ -461,7 +474,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     // is used, the residual values were requested before the last chunk's MFMAs, and ReLU is a
     // maximum with a run-time lower bound, so the write-back is straight-line code.
     if (vec_epi) {
-      const int lo_i = a.relu ? 0 : INT_MIN;
+      const int lo_i = relu ? 0 : INT_MIN;
       auto write_back = [&](auto kind_) {
         constexpr int kind = decltype(kind_)::value;   // 0: int32, 1: f32, 2: bf16
         static_for<MI>([&](auto m_) {
@@ -499,7 +512,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
               if (has_res) r4 += res4[it];
 #pragma unroll
               for (int e = 0; e < 4; ++e) r4[e] = r4[e] > lo_i ? r4[e] : lo_i;
-              if (ok) *reinterpret_cast<i32x4*>(static_cast<int32_t*>(a.out) + addr) = r4;
+              if (ok) *reinterpret_cast<i32x4*>(static_cast<int32_t*>(outp) + addr) = r4;
             } else {
               float f[4];
 #pragma unroll
@@ -511,8 +524,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
                 }
                 i32x4 w4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w4[e] = __float_as_int(a.relu ? fmaxf(f[e], 0.0f) : f[e]);
-                if (ok) *reinterpret_cast<i32x4*>(static_cast<float*>(a.out) + addr) = w4;
+                for (int e = 0; e < 4; ++e) w4[e] = __float_as_int(relu ? fmaxf(f[e], 0.0f) : f[e]);
+                if (ok) *reinterpret_cast<i32x4*>(static_cast<float*>(outp) + addr) = w4;
               } else {
                 if (has_res) {
                   const uint32_t qx = resv[m][it].x, qy = resv[m][it].y;
@@ -520,11 +533,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
                   f[2] += __uint_as_float(qy << 16); f[3] += __uint_as_float(qy & 0xffff0000u);
                 }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) f[e] = a.relu ? fmaxf(f[e], 0.0f) : f[e];
+                for (int e = 0; e < 4; ++e) f[e] = relu ? fmaxf(f[e], 0.0f) : f[e];
                 uint2 w2;
                 w2.x = pack_bf16x2(f[0], f[1]);
                 w2.y = pack_bf16x2(f[2], f[3]);
-                if (ok) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + addr) = w2;
+                if (ok) *reinterpret_cast<uint2*>(static_cast<uint16_t*>(outp) + addr) = w2;
               }
             }
           }
@@ -533,7 +546,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       if constexpr (__is_same(typename TR::acc_t, int32_t)) {
         write_back(std::integral_constant<int, 0>{});
       } else {
-        if (a.out_dtype == GS_BF16) write_back(std::integral_constant<int, 2>{});
+        if (odt == GS_BF16) write_back(std::integral_constant<int, 2>{});
         else write_back(std::integral_constant<int, 1>{});
       }
     } else {
@@ -545,9 +558,9 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           for (int v = 0; v < 16; ++v) {
             const int o = o0 + wo * WOT + m * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             if (pos_ok[n] && o < a.O)
-              store_result<typename TR::acc_t>(a.out, a.residual, a.out_dtype,
+              store_result<typename TR::acc_t>(outp, has_res ? a.residual : nullptr, odt,
                                                out_base[n] + uint32_t(o) * uint32_t(g.HWo), acc[m][n][v],
-                                               a.relu);
+                                               relu);
           }
         });
       });

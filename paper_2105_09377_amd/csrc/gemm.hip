@@ -294,6 +294,8 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
     const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);
     if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4>(a, s);
+    // few rows (a convolution's output channels against many positions): tiles 64 rows tall
+    if (a.I <= 64 && ceil_div(a.J, 256) >= 192) return launch_dma<TR, 64, 256, 1, 4>(a, s);
     if (t128 >= 192) return launch_dma<TR, 128, 128, 2, 2>(a, s);
     return launch_dma<TR, 64, 64, 2, 2>(a, s);
   }

@@ -30,8 +30,6 @@ class ResNet18Stack:
         self.batch, self.image = batch, image
         self.w = {k: v.to(self.dev) for k, v in weights.items()}
         self.spec = {name: (cin, cout, k, s, p) for name, cin, cout, k, s, p in RESNET18_CONVS}
-        # Weights are constants: pack them once, in the order the contraction reads them.
-        self.packed = {name: gs.conv2d_pack_weights(self.w[name]) for name in self.spec if name != "conv1"}
         self.bufs: Dict[str, torch.Tensor] = {}
         self.x = torch.empty((batch, 3, image, image), dtype=torch.bfloat16, device=self.dev)
         h = self._out(image, 7, 2, 3)
@@ -40,6 +38,9 @@ class ResNet18Stack:
         self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         h = self._out(h, 3, 2, 1)
         self._alloc("pool", (batch, 64, h, h))
+        # Weights are constants: pack them once, in the order the contraction reads them, each
+        # into a buffer sized for its layer's call (weights plus that call's scratch).
+        self.packed: Dict[str, torch.Tensor] = {}
         for name, (cin, cout, k, s, p) in self.spec.items():
             if name == "conv1":
                 continue
@@ -48,9 +49,16 @@ class ResNet18Stack:
                 h = self._out(h, k, s, p)
             elif name.endswith("proj"):
                 assert self._out(hin, k, s, p) == h
+            src_hw = hin if name.endswith(("c1", "proj")) else h
+            self.packed[name] = self._pack(name, (batch, cin, src_hw, src_hw), s, p)
             self._alloc(name, (batch, cout, h, h))
         self._alloc("avg", (batch, 512))
         self.logits = torch.empty((batch, self.w["fc"].shape[0]), dtype=torch.float32, device=self.dev)
+
+    def _pack(self, name: str, x_shape: Tuple[int, ...], s: int, p: int) -> torch.Tensor:
+        need = gs.conv2d_workspace(self.x, self.w[name], (s, s), (p, p), x_shape=x_shape)
+        buf = torch.empty(max(need, 16), dtype=torch.uint8, device=self.dev)
+        return gs.conv2d_pack_weights(self.w[name], packed=buf)
 
     @staticmethod
     def _out(h: int, k: int, s: int, p: int) -> int:

@@ -148,6 +148,11 @@ CONV_CASES = [
     ("bf16", 2, 3, 30, 30, 16, 7, 7, (2, 2), (3, 3), torch.bfloat16),   # 7x7/2 pad 3, C = 3
     ("bf16", 1, 48, 9, 11, 20, 3, 2, (1, 2), (0, 1), torch.float32),    # non-square everything
     ("bf16", 2, 128, 12, 12, 64, 3, 3, (1, 1), (1, 1), torch.float32),  # several channel chunks
+    # few output tiles, many chunks: the channel sum is split among workgroups (2 and 4 ways)
+    ("bf16", 2, 256, 7, 7, 128, 3, 3, (1, 1), (1, 1), torch.bfloat16),
+    ("bf16", 3, 128, 8, 8, 96, 3, 3, (1, 1), (1, 1), torch.float32),
+    ("i8", 2, 512, 7, 7, 64, 3, 3, (1, 1), (1, 1), torch.int32),
+    ("bf16", 2, 256, 14, 14, 64, 1, 1, (2, 2), (0, 0), torch.bfloat16),
 ]
 
 
@@ -202,6 +207,27 @@ def test_conv2d_residual_relu(form, dtype, odt):
     conv = pg.conv2d(ap.tensor(to_oracle(x)), ap.tensor(to_oracle(wt)), (1, 1), (1, 1))
     prog = ap.compute(ap.relu, pg.add(conv, ap.access(ap.tensor(to_oracle(res)), 4)))
     assert_parity(got, prog.materialize(), what=f"{form} {dtype} residual+relu")
+
+
+@pytest.mark.parametrize("dtype,odt,hw", [("bf16", torch.bfloat16, 7), ("bf16", torch.float32, 8), ("i8", torch.int32, 8)])
+def test_conv2d_split_channel_sum_residual_relu(dtype, odt, hw):
+    """Split channel sums are combined with the residual and ReLU in a second kernel; and the
+    packed entry point gives the same result with and without the scratch that enables the split."""
+    c = 512 if dtype == "i8" else 256
+    case = (dtype, 2, c, hw, hw, 128, 3, 3, (1, 1), (1, 1), odt)
+    x, wt = conv_inputs(case)
+    shape = (2, 128, hw, hw)
+    res = {torch.int32: lambda: synth.uniform_int32(shape, -50000, 50000, 1611),
+           torch.bfloat16: lambda: synth.normal_bf16(shape, 1.0, 1612),
+           torch.float32: lambda: synth.normal_f32(shape, 1.0, 1613)}[odt]()
+    xd, wd, rd = x.to(DEV), wt.to(DEV), res.to(DEV)
+    assert gs.conv2d_workspace(xd, wd, (1, 1), (1, 1)) > gs.conv2d_pack_weights(wd).numel()   # scratch is asked for
+    got = gs.conv2d_direct(xd, wd, (1, 1), (1, 1), residual=rd, act=gs.GS_ACT_RELU, out_dtype=odt)
+    want = np.maximum(brute.conv2d(to_oracle(x), to_oracle(wt), (1, 1), (1, 1)) + to_oracle(res), 0)
+    assert_parity(got, want, what="split")
+    plain = gs.conv2d_direct_packed(xd, wd, gs.conv2d_pack_weights(wd), (1, 1), (1, 1), residual=rd,
+                                    act=gs.GS_ACT_RELU, out_dtype=odt)
+    assert_parity(plain, want, what="unsplit")
 
 
 def test_conv2d_minus_128_and_empty_batch():
