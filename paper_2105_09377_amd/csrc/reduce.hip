@@ -75,6 +75,32 @@ reduce_rows_group_kernel(const T* __restrict__ in, void* __restrict__ out, int o
   if (row < rows && lane_in_group == 0) store_out<A>(out, out_dtype, row, finish(acc, scale));
 }
 
+// Rows that are whole 16-byte vectors: G lanes per row load 16 bytes each per step (streaming
+// loads: every byte is read once), fold the vector's elements, then combine across the group.
+template <typename T, int G>
+__global__ void __launch_bounds__(256)
+reduce_rows_vec_kernel(const T* __restrict__ in, void* __restrict__ out, int out_dtype, int op,
+                       int64_t rows, int64_t cols, float scale) {
+  using A = typename Elem<T>::acc;
+  constexpr int EPV = 16 / int(sizeof(T));
+  typedef T vec_t __attribute__((ext_vector_type(EPV)));
+  const int lane_in_group = threadIdx.x % G;
+  const int64_t nv = cols / EPV;
+  for (int64_t row = (int64_t(blockIdx.x) * blockDim.x + threadIdx.x) / G; row < rows;
+       row += int64_t(gridDim.x) * blockDim.x / G) {
+    const vec_t* src = reinterpret_cast<const vec_t*>(in + row * cols);
+    A acc = ident<A>(op);
+    for (int64_t v = lane_in_group; v < nv; v += G) {
+      const vec_t x = __builtin_nontemporal_load(src + v);
+#pragma unroll
+      for (int i = 0; i < EPV; ++i) acc = combine(acc, Elem<T>::cvt(x[i]), op);
+    }
+#pragma unroll
+    for (int off = G / 2; off > 0; off >>= 1) acc = combine(acc, __shfl_xor(acc, off, G), op);
+    if (lane_in_group == 0) store_out<A>(out, out_dtype, row, finish(acc, scale));
+  }
+}
+
 // One workgroup of 256 threads per row, for long rows.
 template <typename T>
 __global__ void __launch_bounds__(256)
@@ -98,6 +124,18 @@ reduce_rows_block_kernel(const T* __restrict__ in, void* __restrict__ out, int o
   }
 }
 
+static int reduce_num_cus() {
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
+}
+
 template <typename T>
 static hipError_t launch_reduce_t(const ReduceArgs& a, hipStream_t s) {
   if (a.rows == 0) return hipSuccess;
@@ -105,6 +143,24 @@ static hipError_t launch_reduce_t(const ReduceArgs& a, hipStream_t s) {
 #define GS_LAUNCH_GROUP(G)                                                                       \
   hipLaunchKernelGGL((reduce_rows_group_kernel<T, G>), dim3(unsigned(ceil_div(a.rows * G, 256))), \
                      dim3(256), 0, s, in, a.out, a.out_dtype, a.op, a.rows, a.cols, a.scale)
+  constexpr int EPV = 16 / int(sizeof(T));
+  if (a.cols % EPV == 0 && a.cols >= 8 * EPV && reinterpret_cast<uintptr_t>(a.in) % 16 == 0 &&
+      (a.cols <= 2048 || a.rows >= 1024) && a.cols <= (int64_t(1) << 24)) {
+    const int64_t nv = a.cols / EPV;
+    const int64_t cap = int64_t(reduce_num_cus()) * 32;     // workgroups: enough to fill the chip, rows looped
+#define GS_LAUNCH_VEC(G)                                                                           \
+  {                                                                                                \
+    const int64_t want = ceil_div(a.rows * G, 256);                                                \
+    hipLaunchKernelGGL((reduce_rows_vec_kernel<T, G>), dim3(unsigned(want < cap ? want : cap)),    \
+                       dim3(256), 0, s, in, a.out, a.out_dtype, a.op, a.rows, a.cols, a.scale);    \
+  }
+    if (nv <= 8) GS_LAUNCH_VEC(8)
+    else if (nv <= 16) GS_LAUNCH_VEC(16)
+    else if (nv <= 32) GS_LAUNCH_VEC(32)
+    else GS_LAUNCH_VEC(64)
+#undef GS_LAUNCH_VEC
+    return hipGetLastError();
+  }
   if (a.cols <= 1) GS_LAUNCH_GROUP(1);
   else if (a.cols <= 2) GS_LAUNCH_GROUP(2);
   else if (a.cols <= 4) GS_LAUNCH_GROUP(4);
@@ -346,7 +402,7 @@ pool2d_vec_kernel(Pool2dArgs a) {
       const int ih = ih0 + int(r);
       val[u] = idvec;
       if (id < nvec && ih >= 0 && ih < a.H)
-        val[u] = *reinterpret_cast<const vec_t*>(src + int64_t(ih) * a.W + int(v) * EPV);
+        val[u] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(src + int64_t(ih) * a.W + int(v) * EPV));   // read once
     }
   };
 
@@ -417,7 +473,7 @@ pool2d_vec_kernel(Pool2dArgs a) {
             ov[int(v)] = T(finish(res[v], a.scale));
           }
         });
-        *reinterpret_cast<ovec_t*>(static_cast<T*>(a.out) + o) = ov;
+        __builtin_nontemporal_store(ov, reinterpret_cast<ovec_t*>(static_cast<T*>(a.out) + o));   // written once
       } else {
         static_for<VO>([&](auto v) {
           if (y0 + v < a.Wo) store_out<A>(a.out, a.out_dtype, o + v, finish(res[v], a.scale));
@@ -425,18 +481,6 @@ pool2d_vec_kernel(Pool2dArgs a) {
       }
     }
   }
-}
-
-static int pool_num_cus() {
-  static int cus = 0;
-  if (!cus) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      cus = prop.multiProcessorCount;
-    if (cus <= 0) cus = 256;
-  }
-  return cus;
 }
 
 template <typename T>
@@ -486,8 +530,10 @@ static hipError_t launch_pool2d_t(const WindowsReduceArgs& w, hipStream_t s) {
   // Persistent grid for the vector kernels: what the chip holds at once, by LDS.
   int per_cu = int((160 * 1024) / (lds + 512));
   per_cu = per_cu < 1 ? 1 : per_cu > 8 ? 8 : per_cu;
-  int64_t pgrid = int64_t(pool_num_cus()) * per_cu;
+  int64_t pgrid = int64_t(reduce_num_cus()) * per_cu;
   if (pgrid > a.tasks) pgrid = a.tasks;
+  // Every workgroup gets the same number of tasks: as few workgroups as finish in that many rounds.
+  pgrid = ceil_div(a.tasks, ceil_div(a.tasks, pgrid));
 #define GS_POOL_VEC(KH_, KW_, SH_, SW_, PW_)                                                        \
   if (vec_in && need <= 8 && a.Kh == KH_ && a.Kw == KW_ && a.Sh == SH_ && a.Sw == SW_ &&           \
       a.Pw == PW_ && EPV % SW_ == 0) {                                                             \

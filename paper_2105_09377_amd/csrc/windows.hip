@@ -272,7 +272,8 @@ windows_chw_kernel(WindowsChwArgs a) {
       outv_t v;
 #pragma unroll
       for (int i = 0; i < EPV; ++i) v[i] = *reinterpret_cast<const T*>(lds_raw + (offs[i] + shift));
-      *reinterpret_cast<outv_t*>(out + int64_t(y) * a.ld + kbase + j * EPV) = v;
+      // written once, never read back by this kernel: keep it from displacing the input rows in L2
+      __builtin_nontemporal_store(v, reinterpret_cast<outv_t*>(out + int64_t(y) * a.ld + kbase + j * EPV));
       j += step_j;
       y += step_y;
       if (j >= nchunk) {
@@ -432,6 +433,8 @@ static hipError_t launch_chw_t(const WindowsArgs& w, hipStream_t s) {
   int64_t wgs_per_xcd = int64_t(chw_num_cus()) * per_cu / 8;
   if (wgs_per_xcd > a.per_xcd) wgs_per_xcd = a.per_xcd;
   if (wgs_per_xcd < 1) wgs_per_xcd = 1;
+  // Every workgroup gets the same number of tasks: as few workgroups as finish in that many rounds.
+  wgs_per_xcd = ceil_div(a.per_xcd, ceil_div(a.per_xcd, wgs_per_xcd));
   const dim3 grid(unsigned(wgs_per_xcd) * 8);
   const int64_t need = a.vec_ok ? ceil_div(int64_t(cc) * a.Kh * vpr, 256) : 1;
   if (need <= 3) hipLaunchKernelGGL((windows_chw_kernel<T, 3>), grid, dim3(256), lds, s, a);
