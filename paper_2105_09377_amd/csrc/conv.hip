@@ -166,18 +166,27 @@ hipError_t launch_conv3_i8_t0(const ConvArgs&, const ConvGeom&, hipStream_t);
 hipError_t launch_conv3_i8_t1(const ConvArgs&, const ConvGeom&, hipStream_t);
 hipError_t launch_conv3_i8_t2(const ConvArgs&, const ConvGeom&, hipStream_t);
 
+// 64 x 256 tiles while they number at least three quarters of the compute units.
+static bool conv_prefers_wide_tile(int64_t M, int O) {
+  return ceil_div(M, 256) * ceil_div(O, 64) >= 192;
+}
+
 template <typename TR>
 static hipError_t launch_conv3(const ConvArgs& a, const ConvGeom& g, hipStream_t s) {
   constexpr bool i8 = TR::kEsz == 1;
   if (a.C % (16 / TR::kEsz) != 0 || a.C != a.Cpad) return hipErrorInvalidValue;
+  // Tile shapes: 64 channels x 256 positions (three weight buffers fit, the best pipeline) while
+  // that still gives most compute units a tile; 64 x 128 for small feature maps; 128 x 128 last.
+  auto t0 = [&]() { return i8 ? launch_conv3_i8_t0(a, g, s) : launch_conv3_bf16_t0(a, g, s); };
+  auto t1 = [&]() { return i8 ? launch_conv3_i8_t1(a, g, s) : launch_conv3_bf16_t1(a, g, s); };
+  auto t2 = [&]() { return i8 ? launch_conv3_i8_t2(a, g, s) : launch_conv3_bf16_t2(a, g, s); };
   hipError_t e = hipErrorInvalidValue;
-  if (a.O > 64) {
-    e = i8 ? launch_conv3_i8_t0(a, g, s) : launch_conv3_bf16_t0(a, g, s);
-    if (e != hipErrorInvalidValue) return e;
-  }
-  e = i8 ? launch_conv3_i8_t1(a, g, s) : launch_conv3_bf16_t1(a, g, s);
+  const bool wide = conv_prefers_wide_tile(g.M, a.O);
+  e = wide ? t1() : t2();
   if (e != hipErrorInvalidValue) return e;
-  return i8 ? launch_conv3_i8_t2(a, g, s) : launch_conv3_bf16_t2(a, g, s);
+  e = wide ? t2() : t1();
+  if (e != hipErrorInvalidValue) return e;
+  return a.O > 64 ? t0() : e;
 }
 
 // Combines the partial sums of a split channel sum: out = cvt(relu(sum_k partial[k] + residual)).
@@ -196,7 +205,7 @@ conv_splitk_finish_kernel(const AccT* __restrict__ partial, int ksplit, int64_t 
 
 int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo) {
   const int64_t M = int64_t(N) * Ho * Wo;
-  const int64_t tiles = O > 64 ? ceil_div(M, 128) * ceil_div(O, 128) : ceil_div(M, 256) * ceil_div(O, 64);
+  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O) ? 256 : 128) * ceil_div(O, 64);
   const int nchunk = conv_cpad(in_dtype, C) / (in_dtype == GS_I8 ? 32 : 16);
   const int cus = 256;
   if (tiles * 4 <= cus && nchunk % 16 == 0) return 4;
