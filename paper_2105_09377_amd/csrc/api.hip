@@ -143,10 +143,10 @@ int conv_check_io(const gs_ap* act, const gs_ap* w, const gs_ap* residual, int a
   return GS_OK;
 }
 
-// Row stride of the im2col matrix (and of the padded weight matrix): K rounded up to the 128-byte
-// K slab of the dense kernel.  Columns K..ld are zeros in both operands, so the contraction may
+// Row stride of the im2col matrix (and of the padded weight matrix): K rounded up to the 32-byte
+// K step of the dense kernel.  Columns K..ld are zeros in both operands, so the contraction may
 // run over ld columns and take the direct-to-LDS path.
-int64_t im2col_ld(int dtype, int64_t K) { return round_up(K, 128 / int64_t(dtype_size(dtype))); }
+int64_t im2col_ld(int dtype, int64_t K) { return round_up(K, 32 / int64_t(dtype_size(dtype))); }
 
 }  // namespace
 

@@ -179,7 +179,10 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   const uint8_t* X = static_cast<const uint8_t*>(a.x);
   const uint8_t* Y = static_cast<const uint8_t*>(a.y);
   const int64_t ldxb = a.ldx * TR::kEsz, ldyb = a.ldy * TR::kEsz;
-  const int nslab = int(a.K * TR::kEsz / kSlabBytes);
+  // K is a whole number of 32-byte MFMA steps; the last slab may hold fewer than four of them.
+  const int64_t Kb = a.K * TR::kEsz;
+  const int nslab = int(ceil_div(Kb, kSlabBytes));
+  const int tail_steps = int((Kb - int64_t(nslab - 1) * kSlabBytes) / 32);   // 1..4 steps in the last slab
 
   // Global source of each of this lane's load instructions (rows past the end are clamped: their
   // products land in accumulators that are never stored).
@@ -198,8 +201,11 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
     row = row < a.J ? row : a.J - 1;
     ysrc[q] = Y + row * ldyb + lcol;
   }
+  // In a short last slab the 16-byte columns past K are not multiplied; their lanes re-read
+  // column 0 of the slab instead of running past the end of the row (and of the matrix).
+  const int64_t tail_fix = (((lane & 7) ^ lrow) * 16 >= tail_steps * 32) ? -int64_t(lcol) : 0;
   auto issue_slab = [&](int slab, int buf) {
-    const int64_t k0 = int64_t(slab) * kSlabBytes;
+    const int64_t k0 = int64_t(slab) * kSlabBytes + (slab == nslab - 1 ? tail_fix : 0);
     uint8_t* xs = lds + buf * kBuf + wave * 1024;
     uint8_t* ys = xs + kXBytes;
 #pragma unroll
@@ -230,8 +236,10 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   for (int slab = 0; slab < nslab; ++slab) {
     if (slab + 1 < nslab) issue_slab(slab + 1, (slab + 1) & 1);
     const uint8_t* base = lds + (slab & 1) * kBuf;
+    const int steps = slab == nslab - 1 ? tail_steps : KS;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
+      if (ks >= steps) break;
       i32x4 af[MI], bf[NJ];
 #pragma unroll
       for (int m = 0; m < MI; ++m)
@@ -289,7 +297,7 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
   const bool vec = (a.ldx * TR::kEsz) % 16 == 0 && (a.ldy * TR::kEsz) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.x) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.y) % 16 == 0;
-  const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % kSlabBytes == 0;
+  const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % 32 == 0;   // whole MFMA steps
   if (dma) {
     const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
     const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);

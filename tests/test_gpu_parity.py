@@ -102,6 +102,11 @@ DOT_CASES = [
     ("bf16", (2, 3, 4, 5), 2, (7, 4, 5), 1, torch.float32, False),  # multi-dim access and compute shapes
     ("bf16", (513, 64), 1, (129, 64), 1, torch.bfloat16, True),
     ("i8", (1, 5), 1, (1, 5), 1, torch.int32, False),
+    # K a whole number of 32-byte steps but not of 128-byte slabs: short last slab
+    ("bf16", (70, 80), 1, (300, 80), 1, torch.float32, False),
+    ("bf16", (33, 16), 1, (65, 16), 1, torch.bfloat16, True),
+    ("i8", (129, 96), 1, (140, 96), 1, torch.int32, False),
+    ("bf16", (300, 784), 1, (512, 784), 1, torch.bfloat16, True),
 ]
 
 
