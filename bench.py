@@ -36,17 +36,29 @@ DOM_BATCH = 20                # launches of the dominant kernel per timing graph
 # scaled by the same counter's reading for a plain copy of known size; see profiles/).  A reading
 # only counts for the kernel sources it was taken with: their hash is stored beside it and the
 # bench reports null once the sources differ.
-KERNEL_SOURCES = ("conv_kernels.h", "conv3_inst.hip", "conv.hip", "common.h")
+KERNEL_SOURCES = {
+    "conv": ("conv4_kernel.h", "conv_kernels.h", "conv3_inst.hip", "conv.hip", "common.h"),
+    "windows": ("windows.hip", "common.h"),
+    "reduce": ("reduce.hip", "common.h"),
+    "gemm": ("gemm.hip", "common.h"),
+}
+# workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
+# sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": {"bytes": 60.18e6 + 25.69e6, "sources": "1d7194cd32eaba2d276c8d27464cdc95e7e26341c9c8ec615bea1e0d12463026"},
-    "conv3x3": {"bytes": 24.68e6 + 12.85e6, "sources": None},
+    "resnet18": (60.95e6 + 25.69e6, "conv", "0ee371cb7d21a26edc7c432769cf3e30a9800cf80470939fa065855d727158e3"),       # averaged over the stage-1 launches, half of which read a residual
+    "conv3x3": (24.98e6 + 12.85e6, "conv", "0ee371cb7d21a26edc7c432769cf3e30a9800cf80470939fa065855d727158e3"),
+    "im2col_gather": (12.98e6 + 115.71e6, "windows", "64ce0f6dff9ba7d4307c12863309a468f7c756c5fd61fded4e736d0d6d98564a"),
+    "maxpool": (102.99e6 + 25.69e6, "reduce", "786d40df129464414adc6d1838565a1a1e0e78dc7dfffd49051da6eddca27154"),
+    "reduce": (268.43e6 + 0.52e6, "reduce", "786d40df129464414adc6d1838565a1a1e0e78dc7dfffd49051da6eddca27154"),
+    "dense": (1668.73e6 + 268.44e6, "gemm", "f2d4fe7ab4a5e30d0b2d990aac26304103481cc96a9af9b423cd3fc2a9f43a38"),
+    "mlp_scaled": (29.51e6 + 17.19e6, "gemm", "f2d4fe7ab4a5e30d0b2d990aac26304103481cc96a9af9b423cd3fc2a9f43a38"),
 }
 
 
-def _sources_digest():
+def _sources_digest(group):
     import hashlib
     h = hashlib.sha256()
-    for f in KERNEL_SOURCES:
+    for f in KERNEL_SOURCES[group]:
         with open(os.path.join(ROOT, "paper_2105_09377_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()
@@ -54,7 +66,7 @@ def _sources_digest():
 
 def _traffic(workload):
     t = TRAFFIC.get(workload)
-    return t["bytes"] if t and t["sources"] == _sources_digest() else None
+    return t[0] if t and t[2] == _sources_digest(t[1]) else None
 
 
 def _graph_of(fn, stream):
