@@ -321,7 +321,9 @@ int glenside_conv2d_direct_packed(const gs_ap* act, const gs_ap* w, const int64_
   a.out_dtype = out->dtype;
   a.N = cs.N; a.C = cs.C; a.H = cs.H; a.W = cs.W; a.O = cs.O; a.Kh = cs.Kh; a.Kw = cs.Kw;
   a.Sh = cs.Sh; a.Sw = cs.Sw; a.Ph = cs.Ph; a.Pw = cs.Pw; a.Ho = cs.Ho; a.Wo = cs.Wo;
-  a.Cpad = int(conv_weight_workspace(act->dtype, 1, cs.C, 1, 1) / dtype_size(act->dtype));
+  a.Cpad = int(round_up(cs.C, act->dtype == GS_I8 ? 32 : 16));
+  if (conv_is_smallc(act->dtype, cs.C))
+    a.wnat = static_cast<const uint8_t*>(packed) + conv_smallc_weight_offset(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw);
   a.relu = actfn == GS_ACT_RELU;
   return launch_status(launch_conv(a, static_cast<hipStream_t>(stream)));
 }

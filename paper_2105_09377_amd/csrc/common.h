@@ -207,6 +207,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 struct ConvArgs {
   const void* act;        // N x C x H x W
   const void* wr;         // repacked weights: O x (Kh*Kw) x Cpad, channel fastest, zero padded
+  const void* wnat;       // fewer channels than a chunk: ((O up to 64s),(K up to 32 B)) copy, else null
   void* out;              // N x O x Ho x Wo
   const void* residual;
   int in_dtype, out_dtype;
@@ -217,6 +218,13 @@ struct ConvArgs {
   void* partial;          // ksplit > 1: [ksplit][N*O*Ho*Wo] 32-bit partial sums
 };
 size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw);
+// Few-channel inputs (conv_smallc.hip): a second, natural-order weight copy behind the first.
+bool conv_is_smallc(int in_dtype, int C);
+size_t conv_smallc_weight_bytes(int in_dtype, int O, int C, int Kh, int Kw);
+size_t conv_smallc_weight_offset(int in_dtype, int O, int C, int Kh, int Kw);
+hipError_t launch_conv_smallc_pack(const void* w, void* wn, int in_dtype, int O, int C, int Kh, int Kw,
+                                   hipStream_t s);
+hipError_t launch_conv_smallc(const ConvArgs& a, hipStream_t s);   // reads a.wr = natural-order copy
 hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int C, int Kh, int Kw,
                               hipStream_t s);
 // Returns hipErrorInvalidValue if no tile configuration fits the LDS for this shape.  With

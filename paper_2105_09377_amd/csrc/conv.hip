@@ -53,8 +53,14 @@ static int conv_cpad(int in_dtype, int C) {
   return int(round_up(C, per_step));
 }
 
+size_t conv_smallc_weight_offset(int in_dtype, int O, int C, int Kh, int Kw) {
+  return size_t(round_up(int64_t(O) * Kh * Kw * conv_cpad(in_dtype, C) * int64_t(dtype_size(in_dtype)), 256));
+}
+
 size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw) {
-  return size_t(O) * Kh * Kw * conv_cpad(in_dtype, C) * dtype_size(in_dtype);
+  const size_t tap_major = size_t(O) * Kh * Kw * conv_cpad(in_dtype, C) * dtype_size(in_dtype);
+  const size_t natural = conv_smallc_weight_bytes(in_dtype, O, C, Kh, Kw);
+  return natural ? conv_smallc_weight_offset(in_dtype, O, C, Kh, Kw) + natural : tap_major;
 }
 
 hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int C, int Kh, int Kw,
@@ -70,7 +76,11 @@ hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int 
   else
     hipLaunchKernelGGL((conv_repack_kernel<uint16_t>), grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wr), O, C, Kh * Kw, Cpad);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && conv_is_smallc(in_dtype, C))
+    e = launch_conv_smallc_pack(w, static_cast<uint8_t*>(wr) + conv_smallc_weight_offset(in_dtype, O, C, Kh, Kw),
+                                in_dtype, O, C, Kh, Kw, s);
+  return e;
 }
 
 // Host: most patch rows any tile of TP positions needs, or -1 if a tile spans too many images.
@@ -231,6 +241,12 @@ static hipError_t launch_conv_t(const ConvArgs& a_in, hipStream_t s) {
   g.dHWo = FastDiv::make(uint32_t(g.HWo > 0 ? g.HWo : 1));
   g.dWo = FastDiv::make(uint32_t(a.Wo > 0 ? a.Wo : 1));
   if (g.M == 0 || a.O == 0) return hipSuccess;
+  if (a.wnat) {                        // fewer channels than a chunk: windows formed as im2col rows in LDS
+    ConvArgs b = a;
+    b.wr = a.wnat;
+    const hipError_t es = launch_conv_smallc(b, s);
+    if (es != hipErrorInvalidValue) return es;
+  }
   hipError_t e = launch_conv3<TR>(a, g, s);
   if (a.ksplit > 1) {
     if (e == hipSuccess) {

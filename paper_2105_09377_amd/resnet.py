@@ -2,9 +2,8 @@
 
 Every layer is one access-pattern program of the paper evaluated by the HIP library:
 
-* convolutions are Fig. 2a (`conv2d_direct_packed`, windows formed on chip) -- except the stem,
-  whose 3 input channels are below the direct kernel's channel step and which therefore runs as
-  the im2col-rewritten form of Fig. 5 (`conv2d_im2col`);
+* convolutions are Fig. 2a (`conv2d_direct_packed`, windows formed on chip; the 3-channel stem
+  takes the library's few-channel kernel, which forms im2col rows in LDS);
 * ReLU and the residual addition (the `reduceSum (pair a b)` idiom of Sec. 5.4) are fused into the
   convolution epilogues;
 * max pooling is Fig. 2c (`windows_reduce`), the global average is `compute reduceSum` with a
@@ -34,13 +33,12 @@ class ResNet18Stack:
         self.x = torch.empty((batch, 3, image, image), dtype=torch.bfloat16, device=self.dev)
         h = self._out(image, 7, 2, 3)
         self._alloc("conv1", (batch, 64, h, h))
-        ws = gs.conv2d_workspace(self.x, self.w["conv1"], (2, 2), (3, 3), form="im2col")
-        self.ws = torch.empty(ws, dtype=torch.uint8, device=self.dev)
         h = self._out(h, 3, 2, 1)
         self._alloc("pool", (batch, 64, h, h))
         # Weights are constants: pack them once, in the order the contraction reads them, each
         # into a buffer sized for its layer's call (weights plus that call's scratch).
         self.packed: Dict[str, torch.Tensor] = {}
+        self.packed["conv1"] = self._pack("conv1", tuple(self.x.shape), 2, 3)
         for name, (cin, cout, k, s, p) in self.spec.items():
             if name == "conv1":
                 continue
@@ -79,8 +77,7 @@ class ResNet18Stack:
     def forward(self, x: torch.Tensor = None) -> torch.Tensor:
         if x is not None:
             self.x.copy_(x)
-        y = gs.conv2d_im2col(self.x, self.w["conv1"], (2, 2), (3, 3), act=gs.GS_ACT_RELU,
-                             out=self.bufs["conv1"], workspace=self.ws)
+        y = self._conv("conv1", self.x)
         y = gs.windows_reduce(y, 2, (3, 3), (2, 2), (1, 1), (1, 1), gs.GS_MAX, out=self.bufs["pool"])
         for stage in (1, 2, 3, 4):
             for block in (1, 2):

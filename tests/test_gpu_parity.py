@@ -153,6 +153,12 @@ CONV_CASES = [
     ("bf16", 2, 3, 30, 30, 16, 7, 7, (2, 2), (3, 3), torch.bfloat16),   # 7x7/2 pad 3, C = 3
     ("bf16", 1, 48, 9, 11, 20, 3, 2, (1, 2), (0, 1), torch.float32),    # non-square everything
     ("bf16", 2, 128, 12, 12, 64, 3, 3, (1, 1), (1, 1), torch.float32),  # several channel chunks
+    # fewer channels than a 32-byte chunk: im2col rows formed in LDS (conv_smallc)
+    ("bf16", 2, 1, 19, 23, 5, 3, 3, (1, 1), (1, 1), torch.float32),      # odd width: scalar staging
+    ("bf16", 1, 3, 40, 272, 70, 5, 3, (2, 1), (2, 1), torch.bfloat16),   # two channel tiles, Wo > 128
+    ("bf16", 2, 8, 16, 16, 64, 3, 3, (1, 1), (1, 1), torch.bfloat16),
+    ("i8", 2, 16, 12, 32, 33, 3, 3, (1, 2), (1, 1), torch.int32),
+    ("i8", 1, 3, 9, 9, 4, 1, 1, (1, 1), (0, 0), torch.int32),
     # few output tiles, many chunks: the channel sum is split among workgroups (2 and 4 ways)
     ("bf16", 2, 256, 7, 7, 128, 3, 3, (1, 1), (1, 1), torch.bfloat16),
     ("bf16", 3, 128, 8, 8, 96, 3, 3, (1, 1), (1, 1), torch.float32),
@@ -233,6 +239,17 @@ def test_conv2d_split_channel_sum_residual_relu(dtype, odt, hw):
     plain = gs.conv2d_direct_packed(xd, wd, gs.conv2d_pack_weights(wd), (1, 1), (1, 1), residual=rd,
                                     act=gs.GS_ACT_RELU, out_dtype=odt)
     assert_parity(plain, want, what="unsplit")
+
+
+@pytest.mark.parametrize("odt", [torch.bfloat16, torch.float32])
+def test_conv2d_few_channels_residual_relu(odt):
+    case = ("bf16", 2, 3, 20, 24, 40, 7, 7, (2, 2), (3, 3), odt)
+    x, wt = conv_inputs(case)
+    shape = (2, 40, 10, 12)
+    res = synth.normal_bf16(shape, 1.0, 1621) if odt == torch.bfloat16 else synth.normal_f32(shape, 1.0, 1622)
+    got = gs.conv2d_direct(x.to(DEV), wt.to(DEV), (2, 2), (3, 3), residual=res.to(DEV), act=gs.GS_ACT_RELU, out_dtype=odt)
+    want = np.maximum(brute.conv2d(to_oracle(x), to_oracle(wt), (2, 2), (3, 3)) + to_oracle(res), 0)
+    assert_parity(got, want, what="few channels, residual + relu")
 
 
 def test_conv2d_minus_128_and_empty_batch():
