@@ -97,6 +97,7 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
     const int nvec = nrows * vpr;
 #pragma unroll
     for (int u = 0; u < kSmallCBatch; ++u) {
+      if (u * NT >= nvec) break;                       // uniform: batches past the last vector
       const int id = u * NT + tid;
       uint32_t r, v, c, dx;
       p.dvpr.divmod(uint32_t(id), &r, &v);
@@ -130,6 +131,7 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
       const int nvec = nrows * vpr;
 #pragma unroll
       for (int u = 0; u < kSmallCBatch; ++u) {
+        if (u * NT >= nvec) break;
         const int id = u * NT + tid;
         if (id < nvec) {
           uint32_t r, v;
@@ -158,6 +160,7 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
     {
       const int nchunk = p.Kp / EPV;
       const int items = npos * nchunk;
+#pragma unroll 2
       for (int id = tid; id < items; id += NT) {
         uint32_t pos, j;
         p.dchunk.divmod(uint32_t(id), &pos, &j);
@@ -181,7 +184,7 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
       const uint8_t* ap = wl + (ob_ * 32 + (lane & 31)) * p.wpb + (lane >> 5) * 16;
       const uint8_t* bp = tl + (pb_ * 32 + (lane & 31)) * p.wpb + (lane >> 5) * 16;
       const int ksteps = p.Kp * ESZ / 32;
-#pragma unroll 2
+#pragma unroll 5
       for (int ks = 0; ks < ksteps; ++ks) {
         const i32x4 b = *reinterpret_cast<const i32x4*>(bp + ks * 32);
         const i32x4 a0 = *reinterpret_cast<const i32x4*>(ap + ks * 32);
