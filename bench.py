@@ -45,13 +45,13 @@ KERNEL_SOURCES = {
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (60.95e6 + 25.69e6, "conv", "0ee371cb7d21a26edc7c432769cf3e30a9800cf80470939fa065855d727158e3"),       # averaged over the stage-1 launches, half of which read a residual
-    "conv3x3": (24.98e6 + 12.85e6, "conv", "0ee371cb7d21a26edc7c432769cf3e30a9800cf80470939fa065855d727158e3"),
-    "im2col_gather": (12.98e6 + 115.71e6, "windows", "64ce0f6dff9ba7d4307c12863309a468f7c756c5fd61fded4e736d0d6d98564a"),
-    "maxpool": (102.99e6 + 25.69e6, "reduce", "786d40df129464414adc6d1838565a1a1e0e78dc7dfffd49051da6eddca27154"),
-    "reduce": (268.43e6 + 0.52e6, "reduce", "786d40df129464414adc6d1838565a1a1e0e78dc7dfffd49051da6eddca27154"),
-    "dense": (1668.73e6 + 268.44e6, "gemm", "f2d4fe7ab4a5e30d0b2d990aac26304103481cc96a9af9b423cd3fc2a9f43a38"),
-    "mlp_scaled": (29.51e6 + 17.19e6, "gemm", "f2d4fe7ab4a5e30d0b2d990aac26304103481cc96a9af9b423cd3fc2a9f43a38"),
+    "resnet18": (61.00e6 + 25.69e6, "conv", "264a0be3821e5e29951454e74711dff9ad9fc2aaa5a72c2f5908af785984b312"),       # averaged over the stage-1 launches, half of which read a residual
+    "conv3x3": (24.95e6 + 12.85e6, "conv", "264a0be3821e5e29951454e74711dff9ad9fc2aaa5a72c2f5908af785984b312"),
+    "im2col_gather": (12.98e6 + 115.71e6, "windows", "fae82b7eab63573aea97eec9a938b9e8523fb24bb96ca83e91ccd2373ac3dcae"),
+    "maxpool": (103.00e6 + 25.69e6, "reduce", "790cddbaa5bbf6c9352bd67c848fa1675d9aa1f035410f80eb7cd0ecb9ee4547"),
+    "reduce": (268.43e6 + 0.52e6, "reduce", "790cddbaa5bbf6c9352bd67c848fa1675d9aa1f035410f80eb7cd0ecb9ee4547"),
+    "dense": (1678.71e6 + 268.44e6, "gemm", "2974a61ab0f28b2dd82c533af817353f05287a148f7c6f79aefccb513266460f"),
+    "mlp_scaled": (29.52e6 + 17.20e6, "gemm", "2974a61ab0f28b2dd82c533af817353f05287a148f7c6f79aefccb513266460f"),
 }
 
 
