@@ -237,21 +237,22 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
     if (slab + 1 < nslab) issue_slab(slab + 1, (slab + 1) & 1);
     const uint8_t* base = lds + (slab & 1) * kBuf;
     const int steps = slab == nslab - 1 ? tail_steps : KS;
+    static_for<KS>([&](auto ks_) {
+      constexpr int ks = decltype(ks_)::value;
+      if (ks < steps) {                              // uniform: only the last slab can be short
+        i32x4 af[MI], bf[NJ];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks >= steps) break;
-      i32x4 af[MI], bf[NJ];
+        for (int m = 0; m < MI; ++m)
+          af[m] = *reinterpret_cast<const i32x4*>(base + xrow + m * 32 * kSlabBytes + koff[ks]);
 #pragma unroll
-      for (int m = 0; m < MI; ++m)
-        af[m] = *reinterpret_cast<const i32x4*>(base + xrow + m * 32 * kSlabBytes + koff[ks]);
+        for (int n = 0; n < NJ; ++n)
+          bf[n] = *reinterpret_cast<const i32x4*>(base + yrow + n * 32 * kSlabBytes + koff[ks]);
 #pragma unroll
-      for (int n = 0; n < NJ; ++n)
-        bf[n] = *reinterpret_cast<const i32x4*>(base + yrow + n * 32 * kSlabBytes + koff[ks]);
+        for (int m = 0; m < MI; ++m)
 #pragma unroll
-      for (int m = 0; m < MI; ++m)
-#pragma unroll
-        for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(af[m], bf[n], acc[m][n]);
-    }
+          for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(af[m], bf[n], acc[m][n]);
+      }
+    });
     __syncthreads();   // next slab has landed (the barrier waits for this wave's loads) and
                        // every wave is done reading the current one
   }
