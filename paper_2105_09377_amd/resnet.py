@@ -2,8 +2,11 @@
 
 Every layer is one access-pattern program of the paper evaluated by the HIP library:
 
-* convolutions are Fig. 2a (`conv2d_direct_packed`, windows formed on chip; the 3-channel stem
-  takes the library's few-channel kernel, which forms im2col rows in LDS);
+* 3x3 and 7x7 convolutions are Fig. 2a (`conv2d_direct_packed`, windows formed on chip; the
+  3-channel stem takes the library's few-channel kernel, which forms im2col rows in LDS);
+* the 1x1 stride-2 shortcut projections have no window overlap to exploit, so they run in the
+  im2col-rewritten form of Fig. 5 (`conv2d_im2col`: explicit gather, then the dense contraction),
+  which is the faster of the two forms for them;
 * ReLU and the residual addition (the `reduceSum (pair a b)` idiom of Sec. 5.4) are fused into the
   convolution epilogues;
 * max pooling is Fig. 2c (`windows_reduce`), the global average is `compute reduceSum` with a
@@ -39,6 +42,7 @@ class ResNet18Stack:
         # into a buffer sized for its layer's call (weights plus that call's scratch).
         self.packed: Dict[str, torch.Tensor] = {}
         self.packed["conv1"] = self._pack("conv1", tuple(self.x.shape), 2, 3)
+        ws_bytes = 0
         for name, (cin, cout, k, s, p) in self.spec.items():
             if name == "conv1":
                 continue
@@ -48,8 +52,13 @@ class ResNet18Stack:
             elif name.endswith("proj"):
                 assert self._out(hin, k, s, p) == h
             src_hw = hin if name.endswith(("c1", "proj")) else h
-            self.packed[name] = self._pack(name, (batch, cin, src_hw, src_hw), s, p)
+            if name.endswith("proj"):
+                ws_bytes = max(ws_bytes, gs.conv2d_workspace(self.x, self.w[name], (s, s), (p, p), form="im2col",
+                                                             x_shape=(batch, cin, src_hw, src_hw)))
+            else:
+                self.packed[name] = self._pack(name, (batch, cin, src_hw, src_hw), s, p)
             self._alloc(name, (batch, cout, h, h))
+        self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=self.dev)   # shared by the projections
         self._alloc("avg", (batch, 512))
         self.logits = torch.empty((batch, self.w["fc"].shape[0]), dtype=torch.float32, device=self.dev)
 
@@ -67,6 +76,10 @@ class ResNet18Stack:
 
     def _conv(self, name: str, x: torch.Tensor, residual=None, relu=True) -> torch.Tensor:
         _cin, _cout, k, s, p = self.spec[name]
+        if name.endswith("proj"):
+            return gs.conv2d_im2col(x, self.w[name], (s, s), (p, p), residual=residual,
+                                    act=gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE, out=self.bufs[name],
+                                    workspace=self.ws)
         return gs.conv2d_direct_packed(x, self.w[name], self.packed[name], (s, s), (p, p), residual=residual,
                                        act=gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE, out=self.bufs[name])
 
