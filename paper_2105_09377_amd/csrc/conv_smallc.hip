@@ -97,15 +97,16 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
     const int nvec = nrows * vpr;
 #pragma unroll
     for (int u = 0; u < kSmallCBatch; ++u) {
-      if (u * NT >= nvec) break;                       // uniform: batches past the last vector
-      const int id = u * NT + tid;
-      uint32_t r, v, c, dx;
-      p.dvpr.divmod(uint32_t(id), &r, &v);
-      p.dKh.divmod(r, &c, &dx);
-      const int ih = ho * a.Sh + int(dx) - a.Ph;
       val[u] = i32x4{0, 0, 0, 0};
-      if (id < nvec && ih >= 0 && ih < a.H)
-        val[u] = *reinterpret_cast<const i32x4*>(in + ((int64_t(n) * a.C + int(c)) * a.H + ih) * a.W + int(v) * EPV);
+      if (u * NT < nvec) {                             // uniform: skip batches past the last vector
+        const int id = u * NT + tid;
+        uint32_t r, v, c, dx;
+        p.dvpr.divmod(uint32_t(id), &r, &v);
+        p.dKh.divmod(r, &c, &dx);
+        const int ih = ho * a.Sh + int(dx) - a.Ph;
+        if (id < nvec && ih >= 0 && ih < a.H)
+          val[u] = *reinterpret_cast<const i32x4*>(in + ((int64_t(n) * a.C + int(c)) * a.H + ih) * a.W + int(v) * EPV);
+      }
     }
   };
   if (vec_ok) issue_loads(task);
@@ -131,9 +132,8 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
       const int nvec = nrows * vpr;
 #pragma unroll
       for (int u = 0; u < kSmallCBatch; ++u) {
-        if (u * NT >= nvec) break;
         const int id = u * NT + tid;
-        if (id < nvec) {
+        if (u * NT < nvec && id < nvec) {
           uint32_t r, v;
           p.dvpr.divmod(uint32_t(id), &r, &v);
           int32_t* d = reinterpret_cast<int32_t*>(reinterpret_cast<uint8_t*>(stage) +
@@ -160,7 +160,6 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
     {
       const int nchunk = p.Kp / EPV;
       const int items = npos * nchunk;
-#pragma unroll 2
       for (int id = tid; id < items; id += NT) {
         uint32_t pos, j;
         p.dchunk.divmod(uint32_t(id), &pos, &j);
@@ -184,7 +183,6 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
       const uint8_t* ap = wl + (ob_ * 32 + (lane & 31)) * p.wpb + (lane >> 5) * 16;
       const uint8_t* bp = tl + (pb_ * 32 + (lane & 31)) * p.wpb + (lane >> 5) * 16;
       const int ksteps = p.Kp * ESZ / 32;
-#pragma unroll 5
       for (int ks = 0; ks < ksteps; ++ks) {
         const i32x4 b = *reinterpret_cast<const i32x4*>(bp + ks * 32);
         const i32x4 a0 = *reinterpret_cast<const i32x4*>(ap + ks * 32);

@@ -118,7 +118,7 @@ struct WindowsChwArgs {
   int total;      // N*Ho workgroup tasks
   int per_xcd;    // tasks per XCD (ceil(total / 8))
   uint32_t fill_bits;
-  int vec_ok;     // input rows are whole 16-byte vectors: staged through register prefetch
+  int vec_ok;     // input rows are whole VB-byte vectors: staged through register prefetch
   FastDiv dvpr, dW, dhalo, dKh, dT, dKw;
 };
 
@@ -129,7 +129,7 @@ constexpr int kChwPitchSlack = 8;    // dwords the pitch search may add to a row
 // A workgroup walks over (task, channel pass) units.  While it emits one unit out of LDS, the
 // 16-byte global loads of the next unit are already in flight into registers, so the memory
 // latency of staging overlaps the emit phase instead of preceding it.
-template <typename T, int B>   // B: 16-byte vectors a thread stages per unit
+template <typename T, int B, int VB>   // a thread stages up to B vectors of VB (16, 8 or 4) bytes per unit
 __global__ void __launch_bounds__(256)
 windows_chw_kernel(WindowsChwArgs a) {
   constexpr int ESZ = int(sizeof(T));
@@ -157,14 +157,20 @@ windows_chw_kernel(WindowsChwArgs a) {
 #pragma unroll
   for (int i = 0; i < EPV; ++i) fv[i] = fill;
   const bool vec_ok = a.vec_ok != 0;
-  const int vpr = a.W * ESZ / 16;                       // 16-byte vectors per input row
+  const int vpr = a.W * ESZ / VB;                       // vectors per input row
+  constexpr int VD = VB / 4;                            // dwords per vector
+  constexpr int EPL = VB / ESZ;                         // elements per vector
+  typedef int32_t ldv_t __attribute__((ext_vector_type(VD)));
   const int halo = a.pitch - a.W;                       // cells of an LDS row outside the data
   const int zero_row = (rows_max - 1) * a.pitch;
 
   auto task_valid = [&](int tl) { return tl < a.per_xcd && xcd * a.per_xcd + tl < a.total; };
 
-  // Registers of the unit being fetched: up to B 16-byte vectors per thread.
-  i32x4 val[B];
+  // Registers of the unit being fetched: up to B vectors per thread.
+  ldv_t val[B];
+  ldv_t fillv;
+#pragma unroll
+  for (int i = 0; i < VD; ++i) fillv[i] = __builtin_bit_cast(i32x4, fv)[i];
   auto issue_loads = [&](int tl, int pass) {
     const int task = xcd * a.per_xcd + tl;
     const int n = task / a.Ho, ho = task - n * a.Ho;
@@ -178,10 +184,10 @@ windows_chw_kernel(WindowsChwArgs a) {
       a.dvpr.divmod(uint32_t(id), &r, &v);
       a.dKh.divmod(r, &c, &dx);
       const int ih = ho * a.Sh + int(dx) - a.Ph;
-      val[u] = __builtin_bit_cast(i32x4, fv);
+      val[u] = fillv;
       if (id < nvec && ih >= 0 && ih < a.H)
-        val[u] = *reinterpret_cast<const i32x4*>(
-            in + ((int64_t(n) * a.C + c0 + int(c)) * a.H + ih) * a.W + int(v) * EPV);
+        val[u] = *reinterpret_cast<const ldv_t*>(
+            in + ((int64_t(n) * a.C + c0 + int(c)) * a.H + ih) * a.W + int(v) * EPL);
     }
   };
   auto build_table = [&](int c0, int kbase, int nchunk) {
@@ -233,11 +239,9 @@ windows_chw_kernel(WindowsChwArgs a) {
         if (id < nvec) {
           uint32_t r, v;
           a.dvpr.divmod(uint32_t(id), &r, &v);
-          int32_t* d = reinterpret_cast<int32_t*>(lds_raw + (int(r) * a.pitch + a.XO) * ESZ + int(v) * 16);
-          d[0] = val[u][0];
-          d[1] = val[u][1];
-          d[2] = val[u][2];
-          d[3] = val[u][3];
+          int32_t* d = reinterpret_cast<int32_t*>(lds_raw + (int(r) * a.pitch + a.XO) * ESZ + int(v) * VB);
+#pragma unroll
+          for (int i = 0; i < VD; ++i) d[i] = val[u][i];
         }
       }
     } else {
@@ -384,8 +388,12 @@ static hipError_t launch_chw_t(const WindowsArgs& w, hipStream_t s) {
     const int64_t tab_entries = round_up(int64_t(cc) * a.Kh * a.Kw + (a.ld - K), EPV) + EPV;
     return round_up((int64_t(cc) * a.Kh + 1) * pitch * ESZ, 16) + tab_entries * 4;
   };
-  a.vec_ok = ((a.W * ESZ) % 16 == 0 && reinterpret_cast<uintptr_t>(w.in) % 16 == 0) ? 1 : 0;
-  const int64_t vpr = int64_t(a.W) * ESZ / 16;
+  // Widest vector (16, 8 or 4 bytes) that input rows are whole numbers of and aligned to.
+  int vb = 0;
+  for (int cand = 16; cand >= 4 && !vb; cand /= 2)
+    if ((a.W * ESZ) % cand == 0 && reinterpret_cast<uintptr_t>(w.in) % cand == 0) vb = cand;
+  a.vec_ok = vb ? 1 : 0;
+  const int64_t vpr = vb ? int64_t(a.W) * ESZ / vb : 1;
   const int maxb = kStageBatch;
   auto fits = [&](int c) {
     return bytes_for(c, max_pitch) <= kChwLdsBudget &&
@@ -420,7 +428,7 @@ static hipError_t launch_chw_t(const WindowsArgs& w, hipStream_t s) {
     }
     a.pitch = it->second;
   }
-  a.dvpr = FastDiv::make(uint32_t(a.W * ESZ / 16 > 0 ? a.W * ESZ / 16 : 1));
+  a.dvpr = FastDiv::make(uint32_t(vpr > 0 ? vpr : 1));
   a.dW = FastDiv::make(uint32_t(a.W));
   a.dhalo = FastDiv::make(uint32_t(a.pitch - a.W > 0 ? a.pitch - a.W : 1));
   a.dKh = FastDiv::make(uint32_t(a.Kh));
@@ -437,9 +445,16 @@ static hipError_t launch_chw_t(const WindowsArgs& w, hipStream_t s) {
   wgs_per_xcd = ceil_div(a.per_xcd, ceil_div(a.per_xcd, wgs_per_xcd));
   const dim3 grid(unsigned(wgs_per_xcd) * 8);
   const int64_t need = a.vec_ok ? ceil_div(int64_t(cc) * a.Kh * vpr, 256) : 1;
-  if (need <= 3) hipLaunchKernelGGL((windows_chw_kernel<T, 3>), grid, dim3(256), lds, s, a);
-  else if (need <= 6) hipLaunchKernelGGL((windows_chw_kernel<T, 6>), grid, dim3(256), lds, s, a);
-  else hipLaunchKernelGGL((windows_chw_kernel<T, kStageBatch>), grid, dim3(256), lds, s, a);
+#define GS_CHW_LAUNCH(VB_)                                                                            \
+  {                                                                                                   \
+    if (need <= 3) hipLaunchKernelGGL((windows_chw_kernel<T, 3, VB_>), grid, dim3(256), lds, s, a);   \
+    else if (need <= 6) hipLaunchKernelGGL((windows_chw_kernel<T, 6, VB_>), grid, dim3(256), lds, s, a); \
+    else hipLaunchKernelGGL((windows_chw_kernel<T, kStageBatch, VB_>), grid, dim3(256), lds, s, a);   \
+  }
+  if (vb == 8) GS_CHW_LAUNCH(8)
+  else if (vb == 4) GS_CHW_LAUNCH(4)
+  else GS_CHW_LAUNCH(16)
+#undef GS_CHW_LAUNCH
   return hipGetLastError();
 }
 
