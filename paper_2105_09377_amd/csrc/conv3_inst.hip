@@ -35,10 +35,10 @@ static hipError_t launch_conv3_cfg(const ConvArgs& a, ConvGeom g, hipStream_t s)
 
 // Producer / consumer kernel (eight waves): returns hipErrorInvalidValue when the shape does not
 // fit it.  Three weight buffers when the output-channel tile is 64 wide, two when it is 128.
-template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI>
-static hipError_t launch_conv4_cfg(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes, hipStream_t s) {
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int D>
+static hipError_t launch_conv4_ring(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes, hipStream_t s) {
   constexpr int NWB = TO <= 64 ? 3 : 2;
-  auto kern = conv_direct4_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, NWB>;
+  auto kern = conv_direct4_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, NWB, D>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -52,6 +52,18 @@ static hipError_t launch_conv4_cfg(const ConvArgs& a, const ConvGeom& g, size_t 
   return hipGetLastError();
 }
 
+// Ring depth: four chunks of loads in flight; two when the channel chunks per work item are only
+// a multiple of two (int8 with 64 channels) -- instantiated for int8 only, to bound compile time.
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI>
+static hipError_t launch_conv4_cfg(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes, hipStream_t s) {
+  const int per_item = a.Cpad / (32 / TR::kEsz) / (a.ksplit > 1 ? a.ksplit : 1);
+  if (per_item % 4 == 0) return launch_conv4_ring<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, 4>(a, g, lds_bytes, s);
+  if constexpr (TR::kEsz == 1) {
+    if (per_item % 2 == 0) return launch_conv4_ring<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, 2>(a, g, lds_bytes, s);
+  }
+  return hipErrorInvalidValue;
+}
+
 // Picks the pixel-vector width: a producer thread moves one item of VW pixels x 8 (16) channels
 // per chunk, so the narrowest vector whose items still fit one (then two) per thread keeps the
 // most producer lanes busy.
@@ -60,7 +72,7 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   constexpr int NWB = TO <= 64 ? 3 : 2;
   const int ksplit = a.ksplit > 1 ? a.ksplit : 1;
   const int nchunk = a.Cpad / (32 / TR::kEsz);
-  if (nchunk % (4 * ksplit) != 0) return hipErrorInvalidValue;   // the ring holds four chunks
+  if (nchunk % (2 * ksplit) != 0) return hipErrorInvalidValue;   // the ring holds two or four chunks
   g.max_rows = conv_max_rows(a, g.M, g.HWo, TP);
   if (g.max_rows < 0) return hipErrorInvalidValue;
   const size_t stage_bytes = 4 * 32 * size_t(TP / WP * 4 + 16);   // epilogue staging, one region per wave

@@ -60,12 +60,12 @@ __device__ __forceinline__ bool seg_of_row(const TileSegs& t, int r, const ConvG
   return false;
 }
 
-template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int NWB>
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int NWB, int D>
 __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom g) {
   static_assert(WO * WP == 4, "four consumer waves");
   static_assert(NWB == 2 || NWB == 3, "weight buffers");
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-  constexpr int D = 4;                   // ring depth: chunks of patch loads in flight per thread
+  static_assert(D == 2 || D == 4, "ring depth: chunks of patch loads in flight per thread");
   constexpr int ESZ = TR::kEsz;
   constexpr int G = 16 / ESZ;            // channels per 16-byte vector
   constexpr int CCH = 32 / ESZ;          // channels per chunk
