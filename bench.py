@@ -45,13 +45,13 @@ KERNEL_SOURCES = {
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (61.00e6 + 25.69e6, "conv", "264a0be3821e5e29951454e74711dff9ad9fc2aaa5a72c2f5908af785984b312"),       # averaged over the stage-1 launches, half of which read a residual
-    "conv3x3": (24.95e6 + 12.85e6, "conv", "264a0be3821e5e29951454e74711dff9ad9fc2aaa5a72c2f5908af785984b312"),
-    "im2col_gather": (12.98e6 + 115.71e6, "windows", "fae82b7eab63573aea97eec9a938b9e8523fb24bb96ca83e91ccd2373ac3dcae"),
-    "maxpool": (103.00e6 + 25.69e6, "reduce", "790cddbaa5bbf6c9352bd67c848fa1675d9aa1f035410f80eb7cd0ecb9ee4547"),
-    "reduce": (268.43e6 + 0.52e6, "reduce", "790cddbaa5bbf6c9352bd67c848fa1675d9aa1f035410f80eb7cd0ecb9ee4547"),
-    "dense": (1678.71e6 + 268.44e6, "gemm", "2974a61ab0f28b2dd82c533af817353f05287a148f7c6f79aefccb513266460f"),
-    "mlp_scaled": (29.52e6 + 17.20e6, "gemm", "2974a61ab0f28b2dd82c533af817353f05287a148f7c6f79aefccb513266460f"),
+    "resnet18": (61.05e6 + 25.69e6, "conv", "a58d57754523f51757465d0b83b6ebc3df30ad6b8b5a6500881ea7fead890e17"),       # averaged over the stage-1 launches, half of which read a residual
+    "conv3x3": (24.96e6 + 12.85e6, "conv", "a58d57754523f51757465d0b83b6ebc3df30ad6b8b5a6500881ea7fead890e17"),
+    "im2col_gather": (12.97e6 + 115.70e6, "windows", "2289631241a997f4920db599b721f29dbd164b3a6a0f9e7a040684ec52f9db7f"),
+    "maxpool": (103.00e6 + 25.69e6, "reduce", "cc0d6c2aa3e10cccdb544ca906ee12c66694f665f47dbfcc50025c3ccd7aa8fc"),
+    "reduce": (268.43e6 + 0.52e6, "reduce", "cc0d6c2aa3e10cccdb544ca906ee12c66694f665f47dbfcc50025c3ccd7aa8fc"),
+    "dense": (1616.83e6 + 268.44e6, "gemm", "67bbad542484b97dffbdbcbd2961fc81716453b2bd07448b40a8e08dc7e3dc72"),
+    "mlp_scaled": (29.57e6 + 17.17e6, "gemm", "67bbad542484b97dffbdbcbd2961fc81716453b2bd07448b40a8e08dc7e3dc72"),
 }
 
 

@@ -149,24 +149,30 @@ struct I8Traits {
 
 // Epilogue shared by the contractions: optional residual, optional ReLU, store in the output
 // type.  `addr` is an element offset.
+// `stream`: the result is not read again soon (a large dense product): non-temporal stores keep
+// it from displacing the operands in L2.
 template <typename AccT>
 __device__ __forceinline__ void store_result(void* out, const void* residual, int out_dtype,
-                                             int64_t addr, AccT v, int relu) {
+                                             int64_t addr, AccT v, int relu, bool stream = false) {
   if constexpr (sizeof(AccT) == 4 && __is_same(AccT, int32_t)) {
     int32_t r = v;
     if (residual) r += static_cast<const int32_t*>(residual)[addr];
     if (relu) r = r > 0 ? r : 0;
-    static_cast<int32_t*>(out)[addr] = r;
+    if (stream) __builtin_nontemporal_store(r, static_cast<int32_t*>(out) + addr);
+    else static_cast<int32_t*>(out)[addr] = r;
   } else {
     float r = v;
     if (out_dtype == GS_F32) {
       if (residual) r += static_cast<const float*>(residual)[addr];
       if (relu) r = fmaxf(r, 0.0f);
-      static_cast<float*>(out)[addr] = r;
+      if (stream) __builtin_nontemporal_store(r, static_cast<float*>(out) + addr);
+      else static_cast<float*>(out)[addr] = r;
     } else {
       if (residual) r += bf16_bits_to_float(static_cast<const uint16_t*>(residual)[addr]);
       if (relu) r = fmaxf(r, 0.0f);
-      static_cast<uint16_t*>(out)[addr] = float_to_bf16_bits(r);
+      const uint16_t b = float_to_bf16_bits(r);
+      if (stream) __builtin_nontemporal_store(b, static_cast<uint16_t*>(out) + addr);
+      else static_cast<uint16_t*>(out)[addr] = b;
     }
   }
 }

@@ -258,6 +258,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   }
 
   // Epilogue: lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each block.
+  // Results larger than the last-level cache are streamed past L2.
+  const bool stream_out = a.I * a.J * 4 > (int64_t(128) << 20);
   static_for<NJ>([&](auto n_) {
     constexpr int n = decltype(n_)::value;
     const int64_t j = j0 + wn * WN + n * 32 + (lane & 31);
@@ -271,7 +273,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
         const int64_t i = ibase + 8 * (v >> 2) + (v & 3);
         if (j_ok && i < a.I)
           store_result<typename TR::acc_t>(a.out, a.residual, a.out_dtype, jbase + i * a.jp,
-                                           acc[m][n][v], a.relu);
+                                           acc[m][n][v], a.relu, stream_out);
       }
     });
   });
