@@ -313,7 +313,10 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
             if (sc.chunk <= 1) zero_invalid_rows(sc.tile, sc.chunk);   // first use of this buffer by the tile
             store_patch(std::integral_constant<int, ns>{}, sc.chunk & 1);
           }
-          if (next_unit(sc)) make_items(sc.tile, st);
+          // The store cursor enters a tile D units after the load cursor did and, in program
+          // order, before the load cursor can leave it (chunks per item are a multiple of D):
+          // the load cursor's descriptors are that tile's.
+          if (next_unit(sc)) st = ld;
           {
             const int slot2 = wslot + NWB - 1 >= NWB ? wslot - 1 : wslot + NWB - 1;
             issue_weights(wc.tile, wc.chunk, slot2);
