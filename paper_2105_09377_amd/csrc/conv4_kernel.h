@@ -427,7 +427,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
         constexpr int NT = KH * KW;
         const uint32_t wa = lds_addr_of(wb);
         const uint32_t pa = lds_addr_of(pb);
-        i32x4 fr[2][MI + NJ];
+        constexpr int PD = 2;                      // taps requested ahead of the one being multiplied
+        i32x4 fr[PD + 1][MI + NJ];
         auto request = [&](int tap, int slot) {
           const int kh = tap / KW, kw = tap - kh * KW;
           const uint32_t tapoff = uint32_t((kh * g.PW + kw) * PIXB);
@@ -436,12 +437,12 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
 #pragma unroll
           for (int n = 0; n < NJ; ++n) lds_read_pinned(fr[slot][MI + n], pa + pbase[n] + tapoff);
         };
-        request(0, 0);
+        static_for<(PD < NT ? PD : NT)>([&](auto t_) { request(decltype(t_)::value, decltype(t_)::value); });
         static_for<NT>([&](auto t_) {
           constexpr int t = decltype(t_)::value;
-          constexpr int slot = t % 2;
-          if constexpr (t + 1 < NT) request(t + 1, (t + 1) % 2);
-          constexpr int ahead = t + 1 < NT ? 1 : 0;
+          constexpr int slot = t % (PD + 1);
+          if constexpr (t + PD < NT) request(t + PD, (t + PD) % (PD + 1));
+          constexpr int ahead = (NT - 1 - t) < PD ? (NT - 1 - t) : PD;   // taps requested after tap t
           lds_wait_tied<ahead * (MI + NJ), MI + NJ>(fr[slot]);
 #pragma unroll
           for (int m = 0; m < MI; ++m)
