@@ -1,28 +1,17 @@
-// Host side of the 2D convolution of Fig. 2a (kernels in conv_kernels.h).
-//
-// 2D convolution of Fig. 2a with the windows formed on chip (implicit im2col).
+// Host side of the direct 2D convolution of Fig. 2a: weight packing, kernel selection, and the
+// combine step of split channel sums.
 //
 //   out[n,o,x,y] = sum_{c,dx,dy} act[n,c,Sh*x+dx-Ph,Sw*y+dy-Pw] * w[o,c,dx,dy]
 //
-// The contraction is the same `compute dotProd (cartProd windows weights)` as the dense kernel,
-// with MFMA rows = output channels o and MFMA columns = flattened output positions
-// m = (n, x, y).  Putting the positions on the lanes makes the (N,O,H',W') store of the listing
-// (its squeeze + transpose (0 3 1 2) tail) a coalesced store, because for fixed (n, o) the
-// positions are contiguous in memory.
-//
-// A workgroup (4 waves) owns TO output channels x TP consecutive positions.  For every chunk of
-// input channels it stages in LDS
-//   * the input patch those positions need: whole input rows including the halo, stored
-//     [row][pixel][channel] with the channel fastest.  The NCHW -> channel-fastest transposition
-//     happens in registers between the coalesced global loads (lanes along W) and the 16-byte
-//     LDS writes.  Padded cells are written as zeros, so padding costs nothing later;
-//   * the weight slab [o][tap][channel] from a repacked copy of the weights (workspace).
-// A window element is then just an address into the patch: lane (position) base + tap offset,
-// read 16 bytes (8 bf16 / 16 int8 channels) at a time as the MFMA B operand.  The K order is
-// (channel chunk, dx, dy, channel) -- a reordering of the dotProd sum, exact for integers.
-//
-// A tile of consecutive positions may span several images (small feature maps); the patch is
-// then a list of row segments, one per image, described by a small table in LDS.
+// Kernels, in the order they are tried:
+//   * conv_smallc_kernel  (conv_smallc.hip)  fewer input channels than one 32-byte chunk;
+//   * conv_direct4_kernel (conv4_kernel.h)   eight waves, producers and consumers; may split the
+//                                            channel sum among workgroups;
+//   * conv_direct3_kernel (conv_kernels.h)   four waves doing everything, same LDS layout;
+//   * conv_direct_kernel  (conv_kernels.h)   the simple general kernel.
+// All of them put output channels on MFMA rows and flattened output positions (n, x, y) on MFMA
+// columns (lanes), which makes the (N,O,H',W') store of the listing coalesced, read weights from
+// the packed copy [o][tap][channel] and form windows out of an LDS patch [row][pixel][channel].
 #include "conv_kernels.h"
 
 #include <array>

@@ -2,14 +2,15 @@
 //
 // Both operands are K-contiguous (each access index of a0 / a1 owns one contiguous compute
 // element), which is exactly the operand order the MFMA wants, so tiles are copied global -> LDS
-// with 16-byte loads and no transposition.  A workgroup of 4 waves owns a BM x BN output tile
+// with 16-byte loads and no transposition.  A workgroup of 4 or 8 waves owns a BM x BN output tile
 // (the concat-on-access-dimensions blocking of Sec. 5.4); the K loop walks 128-byte slabs (the
 // pair/reduceSum blocking on the compute dimension), double-buffered in LDS with the next slab's
 // global loads in flight while the current one feeds the MFMAs.  The kernels are written in
 // bytes: a slab row is 128 bytes = 64 bf16 or 128 int8, one MFMA eats 32 bytes of K per row.
 //
 // Two kernels:
-//   gemm_nt_dma_kernel     : aligned operands, K a whole number of slabs.  Slabs go global -> LDS
+//   gemm_nt_dma_kernel     : aligned operands, K a whole number of 32-byte MFMA steps (the last
+//                            slab may be short).  Slabs go global -> LDS
 //                            directly (global_load_lds, 16 bytes per lane, no register staging);
 //                            because such a load writes 64 x 16 contiguous bytes, rows cannot be
 //                            padded, so bank conflicts are avoided by an XOR swizzle of the

@@ -4,6 +4,8 @@
 // Row reductions pick a lane-group width G (power of two, 1..64) no smaller than the row length
 // when it is short, so that the lanes of a wave read consecutive addresses and several rows are
 // reduced per wave with cross-lane shuffles; long rows use one wave (or one workgroup) per row.
+// Rows that are whole 16-byte vectors take a streaming vector kernel; 2D pooling is staged
+// through LDS by persistent workgroups (pool2d_* below).
 #include "common.h"
 
 #include <float.h>
