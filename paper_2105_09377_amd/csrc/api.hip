@@ -238,7 +238,7 @@ int glenside_cartesian_dot(const gs_ap* a0, const gs_ap* a1, gs_ap* out, int act
   } else {
     return GS_ERR_DTYPE;
   }
-  GemmArgs g;
+  GemmArgs g{};
   memset(&g, 0, sizeof(g));
   g.x = a0->data;
   g.y = a1->data;
@@ -400,7 +400,7 @@ int glenside_conv2d_im2col(const gs_ap* act, const gs_ap* w, const int64_t strid
     wmat = wpad;
   }
 
-  GemmArgs g;
+  GemmArgs g{};
   memset(&g, 0, sizeof(g));
   g.x = wmat;
   g.y = cols;

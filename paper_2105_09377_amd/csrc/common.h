@@ -12,6 +12,7 @@
 namespace gs {
 
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x2 __attribute__((ext_vector_type(2)));
 typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -207,6 +208,7 @@ struct GemmArgs {         // C[i][j] = sum_k X[i][k] * Y[j][k]
   int64_t I, J, K, ldx, ldy;
   int64_t jp;             // out element offset = (j / jp) * (I * jp) + i * jp + (j % jp)
   int relu;
+  int vj;                 // set by launch_gemm: columns per lane of the vector write-back (1 = scalar)
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 

@@ -261,6 +261,129 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   // Epilogue: lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each block.
   // Results larger than the last-level cache are streamed past L2.
   const bool stream_out = a.I * a.J * 4 > (int64_t(128) << 20);
+
+  // Vector write-back (a.vj = 8 or 4 consecutive columns j are contiguous and aligned in the
+  // result): each wave stages one 32-row block of its results in the slab memory, which no wave
+  // reads any more, as 32-bit values and writes it back a.vj columns per lane, so a store
+  // instruction carries 16 (or 8) bytes per lane instead of one element.
+  if (a.vj > 1) {
+    constexpr int RS = WN * 4 + 16;                 // staging row stride in bytes
+    static_assert(NW * 32 * RS <= 2 * kBuf, "staging must fit in the slab buffers");
+    uint8_t* stage = lds + wave * (32 * RS);
+    const bool has_res = a.residual != nullptr;
+    auto write_back = [&](auto vj_, auto kind_) {
+      constexpr int VJ = decltype(vj_)::value;       // columns per lane
+      constexpr int kind = decltype(kind_)::value;   // 0: int32, 1: f32, 2: bf16
+      constexpr int NV = VJ / 4;                     // 16-byte pieces of 32-bit values per lane
+      constexpr int LPR = WN / VJ, RPP = 64 / LPR, NP = 32 / RPP;   // lanes per row, rows per pass, passes
+      const int cq = lane % LPR, rsub = lane / LPR;
+      const int64_t jg = j0 + wn * WN + cq * VJ;
+      const bool j_ok = jg < a.J;
+      const int64_t jq = j_ok ? jg : 0;
+      const int64_t jbase = (jq / a.jp) * (a.I * a.jp) + (jq % a.jp);
+      static_for<MI>([&](auto m_) {
+        constexpr int m = decltype(m_)::value;
+        static_for<NJ>([&](auto n_) {
+          constexpr int n = decltype(n_)::value;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            *reinterpret_cast<typename TR::acc_t*>(stage + r * RS + (n * 32 + (lane & 31)) * 4) = acc[m][n][v];
+          }
+        });
+        i32x4 raw[NP][NV];
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
+          for (int q = 0; q < NV; ++q)
+            raw[p][q] = *reinterpret_cast<const i32x4*>(stage + (p * RPP + rsub) * RS + cq * VJ * 4 + q * 16);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const int64_t i = i0 + wm * WM + m * 32 + p * RPP + rsub;
+          const bool ok = j_ok && i < a.I;
+          const int64_t addr = ok ? jbase + i * a.jp : 0;
+          if constexpr (kind == 2) {
+            float f[VJ];
+#pragma unroll
+            for (int e = 0; e < VJ; ++e) f[e] = __int_as_float(raw[p][e >> 2][e & 3]);
+            if (has_res) {
+              uint32_t rq[VJ / 2];
+              if constexpr (VJ == 8) {
+                const i32x4 t = *reinterpret_cast<const i32x4*>(static_cast<const uint16_t*>(a.residual) + addr);
+                rq[0] = t[0]; rq[1] = t[1]; rq[2] = t[2]; rq[3] = t[3];
+              } else {
+                const uint2 t = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a.residual) + addr);
+                rq[0] = t.x; rq[1] = t.y;
+              }
+#pragma unroll
+              for (int e = 0; e < VJ / 2; ++e) {
+                f[2 * e] += __uint_as_float(rq[e] << 16);
+                f[2 * e + 1] += __uint_as_float(rq[e] & 0xffff0000u);
+              }
+            }
+            uint32_t w[VJ / 2];
+#pragma unroll
+            for (int e = 0; e < VJ / 2; ++e) {
+              const float lo = a.relu ? fmaxf(f[2 * e], 0.0f) : f[2 * e];
+              const float hi = a.relu ? fmaxf(f[2 * e + 1], 0.0f) : f[2 * e + 1];
+              w[e] = pack_bf16x2(lo, hi);
+            }
+            if (ok) {
+              uint16_t* dst = static_cast<uint16_t*>(a.out) + addr;
+              if constexpr (VJ == 8) {
+                const i32x4 w4 = {int(w[0]), int(w[1]), int(w[2]), int(w[3])};
+                if (stream_out) __builtin_nontemporal_store(w4, reinterpret_cast<i32x4*>(dst));
+                else *reinterpret_cast<i32x4*>(dst) = w4;
+              } else {
+                const i32x2 w2 = {int(w[0]), int(w[1])};
+                if (stream_out) __builtin_nontemporal_store(w2, reinterpret_cast<i32x2*>(dst));
+                else *reinterpret_cast<i32x2*>(dst) = w2;
+              }
+            }
+          } else {
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+              i32x4 r4 = raw[p][q];
+              if (has_res) {
+                const i32x4 t = *reinterpret_cast<const i32x4*>(static_cast<const int32_t*>(a.residual) + addr + q * 4);
+                if constexpr (kind == 0) {
+                  r4 += t;
+                } else {
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) r4[e] = __float_as_int(__int_as_float(r4[e]) + __int_as_float(t[e]));
+                }
+              }
+              if (a.relu) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  if constexpr (kind == 0) r4[e] = r4[e] > 0 ? r4[e] : 0;
+                  else r4[e] = __float_as_int(fmaxf(__int_as_float(r4[e]), 0.0f));
+                }
+              }
+              if (ok) {
+                i32x4* dst = reinterpret_cast<i32x4*>(static_cast<int32_t*>(a.out) + addr + q * 4);
+                if (stream_out) __builtin_nontemporal_store(r4, dst);
+                else *dst = r4;
+              }
+            }
+          }
+        }
+      });
+    };
+    using c8 = std::integral_constant<int, 8>;
+    using c4 = std::integral_constant<int, 4>;
+    if constexpr (__is_same(typename TR::acc_t, int32_t)) {
+      if (a.vj == 8) write_back(c8{}, std::integral_constant<int, 0>{});
+      else write_back(c4{}, std::integral_constant<int, 0>{});
+    } else if (a.out_dtype == GS_BF16) {
+      if (a.vj == 8) write_back(c8{}, std::integral_constant<int, 2>{});
+      else write_back(c4{}, std::integral_constant<int, 2>{});
+    } else {
+      if (a.vj == 8) write_back(c8{}, std::integral_constant<int, 1>{});
+      else write_back(c4{}, std::integral_constant<int, 1>{});
+    }
+    return;
+  }
   static_for<NJ>([&](auto n_) {
     constexpr int n = decltype(n_)::value;
     const int64_t j = j0 + wn * WN + n * 32 + (lane & 31);
@@ -296,6 +419,18 @@ static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Tile choice of the direct-to-LDS kernel.
+template <typename TR>
+static hipError_t launch_dma_tiles(const GemmArgs& a, hipStream_t s) {
+  const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
+  const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);
+  if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4>(a, s);
+  // few rows (a convolution's output channels against many positions): tiles 64 rows tall
+  if (a.I <= 64 && ceil_div(a.J, 256) >= 192) return launch_dma<TR, 64, 256, 1, 4>(a, s);
+  if (t128 >= 192) return launch_dma<TR, 128, 128, 2, 2>(a, s);
+  return launch_dma<TR, 64, 64, 2, 2>(a, s);
+}
+
 template <typename TR>
 static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
   const bool vec = (a.ldx * TR::kEsz) % 16 == 0 && (a.ldy * TR::kEsz) % 16 == 0 &&
@@ -303,13 +438,18 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
                    reinterpret_cast<uintptr_t>(a.y) % 16 == 0;
   const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % 32 == 0;   // whole MFMA steps
   if (dma) {
-    const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
-    const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);
-    if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4>(a, s);
-    // few rows (a convolution's output channels against many positions): tiles 64 rows tall
-    if (a.I <= 64 && ceil_div(a.J, 256) >= 192) return launch_dma<TR, 64, 256, 1, 4>(a, s);
-    if (t128 >= 192) return launch_dma<TR, 128, 128, 2, 2>(a, s);
-    return launch_dma<TR, 64, 64, 2, 2>(a, s);
+    // Columns per lane of the vector write-back: groups of vj columns must not straddle a jp
+    // boundary or the end of the result, and must be 16-byte (8-byte for 4 bfloat16) aligned.
+    GemmArgs v = a;
+    v.vj = 1;
+    const size_t osz = dtype_size(a.out_dtype);
+    for (int cand = 8; cand >= 4 && v.vj == 1; cand /= 2) {
+      const size_t al = cand * osz < 16 ? cand * osz : 16;
+      if (a.jp % cand == 0 && a.J % cand == 0 && reinterpret_cast<uintptr_t>(a.out) % al == 0 &&
+          reinterpret_cast<uintptr_t>(a.residual) % al == 0)
+        v.vj = cand;
+    }
+    return launch_dma_tiles<TR>(v, s);
   }
   const int64_t tiles = ceil_div(a.I, 64) * ceil_div(a.J, 64);
   if (vec)

@@ -107,6 +107,10 @@ DOT_CASES = [
     ("bf16", (33, 16), 1, (65, 16), 1, torch.bfloat16, True),
     ("i8", (129, 96), 1, (140, 96), 1, torch.int32, False),
     ("bf16", (300, 784), 1, (512, 784), 1, torch.bfloat16, True),
+    # result rows written 8 and 4 columns per lane, in every result type
+    ("i8", (64, 128), 1, (72, 128), 1, torch.int32, True),
+    ("bf16", (40, 64), 1, (76, 64), 1, torch.bfloat16, False),
+    ("bf16", (200, 256), 1, (264, 256), 1, torch.float32, False),
 ]
 
 
@@ -203,16 +207,17 @@ def test_conv2d_direct_equals_im2col_bitwise_int8():
 
 
 @pytest.mark.parametrize("form", ["direct", "im2col"])
+@pytest.mark.parametrize("hw", [10, 12, 9])    # planes of 100, 144, 81 positions: 4, 8, 1 results per store
 @pytest.mark.parametrize("dtype,odt", [("i8", torch.int32), ("bf16", torch.bfloat16), ("bf16", torch.float32)])
-def test_conv2d_residual_relu(form, dtype, odt):
-    case = (dtype, 2, 32, 10, 10, 40, 3, 3, (1, 1), (1, 1), odt)
+def test_conv2d_residual_relu(form, dtype, odt, hw):
+    case = (dtype, 2, 32, hw, hw, 40, 3, 3, (1, 1), (1, 1), odt)
     x, wt = conv_inputs(case)
     if odt == torch.int32:
-        res = synth.uniform_int32((2, 40, 10, 10), -50000, 50000, 1601)
+        res = synth.uniform_int32((2, 40, hw, hw), -50000, 50000, 1601)
     elif odt == torch.bfloat16:
-        res = synth.normal_bf16((2, 40, 10, 10), 1.0, 1602)
+        res = synth.normal_bf16((2, 40, hw, hw), 1.0, 1602)
     else:
-        res = synth.normal_f32((2, 40, 10, 10), 1.0, 1603)
+        res = synth.normal_f32((2, 40, hw, hw), 1.0, 1603)
     fn = gs.conv2d_direct if form == "direct" else gs.conv2d_im2col
     got = fn(x.to(DEV), wt.to(DEV), (1, 1), (1, 1), residual=res.to(DEV), act=gs.GS_ACT_RELU, out_dtype=odt)
     conv = pg.conv2d(ap.tensor(to_oracle(x)), ap.tensor(to_oracle(wt)), (1, 1), (1, 1))
