@@ -35,10 +35,10 @@ static hipError_t launch_conv3_cfg(const ConvArgs& a, ConvGeom g, hipStream_t s)
 
 // Producer / consumer kernel (eight waves): returns hipErrorInvalidValue when the shape does not
 // fit it.  Three weight buffers when the output-channel tile is 64 wide, two when it is 128.
-template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int D>
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int D, bool FLAT>
 static hipError_t launch_conv4_ring(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes, hipStream_t s) {
   constexpr int NWB = TO <= 64 ? 3 : 2;
-  auto kern = conv_direct4_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, NWB, D>;
+  auto kern = conv_direct4_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, NWB, D, FLAT>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -54,19 +54,20 @@ static hipError_t launch_conv4_ring(const ConvArgs& a, const ConvGeom& g, size_t
 
 // Ring depth: four chunks of loads in flight; two when the channel chunks per work item are only
 // a multiple of two (int8 with 64 channels) -- instantiated for int8 only, to bound compile time.
-template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI>
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, bool FLAT = false>
 static hipError_t launch_conv4_cfg(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes, hipStream_t s) {
   const int per_item = a.Cpad / (32 / TR::kEsz) / (a.ksplit > 1 ? a.ksplit : 1);
-  if (per_item % 4 == 0) return launch_conv4_ring<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, 4>(a, g, lds_bytes, s);
+  if (per_item % 4 == 0)
+    return launch_conv4_ring<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, 4, FLAT>(a, g, lds_bytes, s);
   if constexpr (TR::kEsz == 1) {
-    if (per_item % 2 == 0) return launch_conv4_ring<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, 2>(a, g, lds_bytes, s);
+    if (per_item % 2 == 0)
+      return launch_conv4_ring<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, 2, FLAT>(a, g, lds_bytes, s);
   }
   return hipErrorInvalidValue;
 }
 
-// Picks the pixel-vector width: a producer thread moves one item of VW pixels x 8 (16) channels
-// per chunk, so the narrowest vector whose items still fit one (then two) per thread keeps the
-// most producer lanes busy.
+// Picks the shape of the producers' items: a producer thread moves one or two items of VW pixels
+// x 8 (16) channels per chunk.
 template <typename TR, int TO, int TP, int WO, int WP, int KH, int KW>
 static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   constexpr int NWB = TO <= 64 ? 3 : 2;
@@ -79,13 +80,28 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   const size_t patch_bytes = 2 * size_t(g.max_rows) * g.PW * 48;
   const size_t lds_bytes = 1024 + NWB * size_t(a.Kh * a.Kw) * TO * 32 + patch_bytes + stage_bytes;
   if (lds_bytes > size_t(kLdsLimit)) return hipErrorInvalidValue;
+  // A producer thread issues 8 (16 for int8) loads per item whatever the item's width, and those
+  // instructions are what limits it: one item per thread beats two.  Aligned items (VW pixels of
+  // one row, W a multiple of VW) are tried narrowest first, which keeps the most lanes busy; then
+  // items of 4 or 8 pixels consecutive in memory, which cross row ends and need no alignment;
+  // then two items per thread.
   auto items = [&](int vw) { return int64_t(g.max_rows) * (a.W / vw) * 2; };
+  // Every segment of a tile (one per image it touches) may end with a partial flat item per
+  // channel group.
+  const int64_t segs = (TP + g.HWo - 2) / g.HWo + 1;
+  auto flat_items = [&](int vw) { return 2 * ((int64_t(g.max_rows) * a.W + vw - 1) / vw + segs); };
 #define GS_TRY(VW_, MAXI_)                                                                   \
   if (a.W % VW_ == 0 && items(VW_) <= 256 * MAXI_)                                          \
     return launch_conv4_cfg<TR, TO, TP, WO, WP, VW_, KH, KW, MAXI_>(a, g, lds_bytes, s);
+#define GS_TRY_FLAT(VW_, MAXI_)                                                              \
+  if (a.W >= VW_ && flat_items(VW_) <= 256 * MAXI_)                                         \
+    return launch_conv4_cfg<TR, TO, TP, WO, WP, VW_, KH, KW, MAXI_, true>(a, g, lds_bytes, s);
   GS_TRY(1, 1) GS_TRY(2, 1) GS_TRY(4, 1) GS_TRY(8, 1)
+  GS_TRY_FLAT(4, 1) GS_TRY_FLAT(8, 1)
   GS_TRY(1, 2) GS_TRY(2, 2) GS_TRY(4, 2)   // (8, 2) would need 256 ring registers
+  GS_TRY_FLAT(4, 2)
 #undef GS_TRY
+#undef GS_TRY_FLAT
   return hipErrorInvalidValue;
 }
 

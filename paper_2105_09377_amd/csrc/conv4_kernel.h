@@ -60,7 +60,12 @@ __device__ __forceinline__ bool seg_of_row(const TileSegs& t, int r, const ConvG
   return false;
 }
 
-template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int NWB, int D>
+// FLAT: a producer item is VW pixels that are consecutive in memory (the valid rows of a segment
+// are one contiguous range of the channel plane) rather than VW pixels of one row, so rows whose
+// width is not a multiple of VW are still moved with wide loads.  Such loads are aligned to the
+// element size only, and each pixel of an item has its own LDS destination.
+template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, int MAXI, int NWB, int D,
+          bool FLAT = false>
 __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom g) {
   static_assert(WO * WP == 4, "four consumer waves");
   static_assert(NWB == 2 || NWB == 3, "weight buffers");
@@ -133,9 +138,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     struct Cursor {
       int tile, chunk;
     };
+    constexpr int ND = FLAT ? VW : 1;                   // LDS destinations kept per item
+    const FastDiv dW = FastDiv::make(uint32_t(a.W));
     struct Items {
       const uint8_t* src[MAXI];
-      int dst[MAXI];
+      int dst[MAXI][ND];
       uint32_t okbits;          // bit i: item i exists
     };
     auto make_items = [&](int tile_, Items& it) {
@@ -143,11 +150,47 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       tile_range(tile_, &m0_, &mend_, &o0_);
       const TileSegs ts = tile_segs(m0_, mend_, g);
       it.okbits = 0;
+      if constexpr (FLAT) {
+        // Segment s contributes ceil(L / VW) items per channel group, L = pixels of its valid
+        // rows; the last item of a range is moved back to end with the range (it overlaps its
+        // neighbour, which is written twice with the same data) so that no load leaves the range.
+#pragma unroll
+        for (int i = 0; i < MAXI; ++i) {
+          it.src[i] = act;
+#pragma unroll
+          for (int e = 0; e < ND; ++e) it.dst[i][e] = 512 + e * PIXB;   // dummy area
+          int rem = ptid + 256 * i, base = 0;
+          bool found = false;
+          for (int s_ = 0; s_ < ts.nseg; ++s_) {
+            int ihlo, rows;
+            seg_extent(ts, s_, g, a.Sh, a.Ph, a.Kh, &ihlo, &rows);
+            const int vlo = ihlo > 0 ? ihlo : 0;
+            const int vhi = ihlo + rows < a.H ? ihlo + rows : a.H;
+            const int L = vhi > vlo ? (vhi - vlo) * a.W : 0;
+            const int cnt = (L + VW - 1) / VW;
+            if (!found && rem < 2 * cnt) {
+              found = true;
+              const int cg = rem >= cnt ? 1 : 0, k = rem - cg * cnt;
+              const int f0 = vlo * a.W + (k * VW < L - VW ? k * VW : L - VW);
+              it.okbits |= 1u << i;
+              it.src[i] = act + (int64_t(ts.n_first + s_) * a.C + cg * G) * plane + int64_t(f0) * ESZ;
+#pragma unroll
+              for (int e = 0; e < ND; ++e) {
+                const int row = int(dW.div(uint32_t(f0 + e))), col = f0 + e - row * a.W;
+                it.dst[i][e] = int(pl - lds) + ((base + row - ihlo) * g.PW + g.XO + col) * PIXB + cg * 16;
+              }
+            }
+            rem -= 2 * cnt;
+            base += rows;
+          }
+        }
+        return;
+      }
 #pragma unroll
       for (int i = 0; i < MAXI; ++i) {
         const int id = ptid + 256 * i;
         it.src[i] = act;
-        it.dst[i] = 512;          // dummy area (VW * 48 bytes at most)
+        it.dst[i][0] = 512;       // dummy area (VW * 48 bytes at most)
         const int rc = int(dXG.div(uint32_t(id))), xg = id - rc * XGn;
         const int cg = rc & 1, r = rc >> 1;
         int s, ih;
@@ -155,7 +198,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           it.okbits |= 1u << i;
           it.src[i] = act + (int64_t(ts.n_first + s) * a.C + cg * G) * plane +
                       (int64_t(ih) * a.W + xg * VW) * ESZ;
-          it.dst[i] = int(pl - lds) + (r * g.PW + g.XO + xg * VW) * PIXB + cg * 16;
+          it.dst[i][0] = int(pl - lds) + (r * g.PW + g.XO + xg * VW) * PIXB + cg * 16;
         }
       }
     };
@@ -243,7 +286,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       constexpr int slot = decltype(slot_)::value;
 #pragma unroll
       for (int i = 0; i < MAXI; ++i) {
-        uint8_t* pb = lds + st.dst[i] + (((st.okbits >> i) & 1u) ? buf * pbytes : 0);
+        const int boff_ = ((st.okbits >> i) & 1u) ? buf * pbytes : 0;
+        uint8_t* pb = lds + st.dst[i][0] + boff_;
 #pragma unroll
         for (int p = 0; p < VW; ++p) {
           i32x4 v;   // pixel p: element t = channel t of the group
@@ -260,7 +304,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
             }
             v[d] = int32_t(w);
           }
-          *reinterpret_cast<i32x4*>(pb + p * PIXB) = v;
+          if constexpr (FLAT) *reinterpret_cast<i32x4*>(lds + st.dst[i][p] + boff_) = v;
+          else *reinterpret_cast<i32x4*>(pb + p * PIXB) = v;
         }
       }
     };

@@ -168,6 +168,12 @@ CONV_CASES = [
     ("bf16", 3, 128, 8, 8, 96, 3, 3, (1, 1), (1, 1), torch.float32),
     ("i8", 2, 512, 7, 7, 64, 3, 3, (1, 1), (1, 1), torch.int32),
     ("bf16", 2, 256, 14, 14, 64, 1, 1, (2, 2), (0, 0), torch.bfloat16),
+    # odd widths: rows moved as runs of four pixels that cross row ends, unaligned loads
+    ("bf16", 3, 64, 9, 7, 70, 3, 3, (1, 1), (1, 1), torch.bfloat16),
+    ("bf16", 2, 64, 15, 13, 64, 3, 3, (2, 2), (1, 1), torch.float32),
+    ("bf16", 7, 64, 7, 7, 32, 5, 5, (1, 1), (2, 2), torch.float32),
+    ("bf16", 1, 64, 33, 45, 48, 3, 3, (1, 1), (0, 0), torch.bfloat16),
+    ("i8", 2, 128, 7, 9, 33, 3, 3, (1, 1), (1, 1), torch.int32),
 ]
 
 
