@@ -290,19 +290,21 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
         uint8_t* pb = lds + st.dst[i][0] + boff_;
 #pragma unroll
         for (int p = 0; p < VW; ++p) {
-          i32x4 v;   // pixel p: element t = channel t of the group
+          i32x4 v;   // pixel p: element t = channel t of the group; one byte permute per two sources
+          const int boff = p * ESZ, wi = boff / 4, bk = boff % 4;
 #pragma unroll
           for (int d = 0; d < 4; ++d) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int e = 0; e < 4 / ESZ; ++e) {
-              const int t = d * (4 / ESZ) + e;
-              const int boff = p * ESZ;
-              const uint32_t word = preg[slot][i][t].word(boff / 4);
-              const uint32_t val = (word >> ((boff % 4) * 8)) & (ESZ == 2 ? 0xffffu : 0xffu);
-              w |= val << (e * ESZ * 8);
+            if constexpr (ESZ == 2) {
+              const uint32_t c0 = preg[slot][i][2 * d].word(wi), c1 = preg[slot][i][2 * d + 1].word(wi);
+              v[d] = int32_t(__builtin_amdgcn_perm(c1, c0, bk ? 0x07060302u : 0x05040100u));
+            } else {
+              const uint32_t sel = uint32_t((4 + bk) << 8 | bk);
+              const uint32_t t01 = __builtin_amdgcn_perm(preg[slot][i][4 * d + 1].word(wi),
+                                                         preg[slot][i][4 * d].word(wi), sel);
+              const uint32_t t23 = __builtin_amdgcn_perm(preg[slot][i][4 * d + 3].word(wi),
+                                                         preg[slot][i][4 * d + 2].word(wi), sel);
+              v[d] = int32_t(__builtin_amdgcn_perm(t23, t01, 0x05040100u));
             }
-            v[d] = int32_t(w);
           }
           if constexpr (FLAT) *reinterpret_cast<i32x4*>(lds + st.dst[i][p] + boff_) = v;
           else *reinterpret_cast<i32x4*>(pb + p * PIXB) = v;
