@@ -103,8 +103,17 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   uint8_t* pl = wl + NWB * wbytes;                    // [2][pbytes]
   uint8_t* sl = pl + 2 * pbytes;                      // [4][32 * RS] epilogue staging
 
+  // Work item i runs on XCD i % 8 (workgroups are dealt to the 8 XCDs, each with its own L2, in
+  // turn, and the grid is a multiple of 8 or a single round).  `lg` renumbers the items so that an
+  // XCD owns a contiguous range of the (channel tile, position tile, split) order: its workgroups
+  // then share one or two channel tiles' weights and neighbouring patches in that L2.
+  const int xcd_per = n_tiles >> 3, xcd_rem = n_tiles & 7;
+  auto lg = [&](int i) {
+    const int x = i & 7;
+    return x * xcd_per + (x < xcd_rem ? x : xcd_rem) + (i >> 3);
+  };
   auto tile_range = [&](int item, int* m0, int* mend, int* o0) {
-    const int tile = item >> kshift;
+    const int tile = lg(item) >> kshift;
     const int to = int(dTiles.div(uint32_t(tile)));
     *m0 = (tile - to * tiles_m) * TP;
     *o0 = to * TO;
@@ -249,7 +258,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     WSrc wld;
     const uint32_t wl_addr = lds_addr_of(wl);
     auto issue_weights = [&](int item, int chunk, int slot) {
-      const int64_t coff = int64_t((item & (ksplit - 1)) * nchunk + chunk) * CCH * ESZ;
+      const int64_t coff = int64_t((lg(item) & (ksplit - 1)) * nchunk + chunk) * CCH * ESZ;
       auto one = [&](int q) {
         const int tap = q / OB, b = q % OB;
         const uint8_t* src = wld.p[0];
@@ -270,7 +279,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
 
     RingReg<LB> preg[D][MAXI][G];
     Items ld, st;             // items of the tile being loaded and of the tile being stored
-    auto chunk_base = [&](int item) { return (item & (ksplit - 1)) * nchunk; };
+    auto chunk_base = [&](int item) { return (lg(item) & (ksplit - 1)) * nchunk; };
     auto load_patch = [&](int item, int chunk, auto slot_) {
       constexpr int slot = decltype(slot_)::value;
       const int64_t coff = int64_t(chunk_base(item) + chunk) * CCH * plane;
@@ -443,7 +452,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     // (raw 32-bit sums; residual, ReLU and the conversion happen when the slices are combined).
     const bool split = ksplit > 1;
     void* const outp = split ? static_cast<void*>(static_cast<int32_t*>(a.partial) +
-                                                   int64_t(tile & (ksplit - 1)) * a.N * a.O * g.HWo)
+                                                   int64_t(lg(tile) & (ksplit - 1)) * a.N * a.O * g.HWo)
                              : a.out;
     const int odt = split ? (__is_same(typename TR::acc_t, int32_t) ? GS_I32 : GS_F32) : a.out_dtype;
     const bool relu = !split && a.relu;
