@@ -58,7 +58,10 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
   const int halo = p.pitch - a.W;
   const bool vec_ok = p.vec_ok != 0;
 
+  // Workgroup b runs on XCD b % 8.  Within each round of gridDim.x tasks an XCD takes a contiguous
+  // run of them, so that the input rows shared by neighbouring output rows meet in one L2.
   int64_t task = blockIdx.x;
+  if (gridDim.x % 8 == 0) task = int64_t(blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
   if (task >= p.tasks) return;
   // task -> (o tile, n, x, position tile): the channel tile changes slowest so that a workgroup
   // almost never reloads its weights

@@ -214,9 +214,10 @@ def test_conv2d_direct_equals_im2col_bitwise_int8():
 
 @pytest.mark.parametrize("form", ["direct", "im2col"])
 @pytest.mark.parametrize("hw", [10, 12, 9])    # planes of 100, 144, 81 positions: 4, 8, 1 results per store
+@pytest.mark.parametrize("c", [32, 128])     # 128 channels: enough chunks for the producer / consumer kernel
 @pytest.mark.parametrize("dtype,odt", [("i8", torch.int32), ("bf16", torch.bfloat16), ("bf16", torch.float32)])
-def test_conv2d_residual_relu(form, dtype, odt, hw):
-    case = (dtype, 2, 32, hw, hw, 40, 3, 3, (1, 1), (1, 1), odt)
+def test_conv2d_residual_relu(form, dtype, odt, hw, c):
+    case = (dtype, 2, c, hw, hw, 40, 3, 3, (1, 1), (1, 1), odt)
     x, wt = conv_inputs(case)
     if odt == torch.int32:
         res = synth.uniform_int32((2, 40, hw, hw), -50000, 50000, 1601)
