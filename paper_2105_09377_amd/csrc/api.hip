@@ -259,7 +259,7 @@ size_t glenside_conv2d_direct_workspace(const gs_ap* act, const gs_ap* w, const 
   ConvShape cs;
   if (conv_shape(act, w, stride, pad, &cs)) return 0;
   const int64_t wbytes = round_up(int64_t(conv_weight_workspace(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw)), 256) + 256;
-  const int ks = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo);
+  const int ks = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo, cs.Sh * cs.Sw == 1);
   const int64_t scratch = ks > 1 ? int64_t(ks) * cs.N * cs.O * cs.Ho * cs.Wo * 4 : 0;
   return size_t(wbytes + scratch);
 }
@@ -310,7 +310,7 @@ int glenside_conv2d_direct_packed(const gs_ap* act, const gs_ap* w, const int64_
   memset(&a, 0, sizeof(a));
   a.ksplit = 1;
   if (need > wneed && packed_bytes >= need) {
-    a.ksplit = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo);
+    a.ksplit = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo, cs.Sh * cs.Sw == 1);
     a.partial = static_cast<uint8_t*>(packed) + wneed;
   }
   a.act = act->data;

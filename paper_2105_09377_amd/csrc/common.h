@@ -240,7 +240,7 @@ hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int 
 // blocking rule: partial dot products combined by reduceSum over a pair); others ignore it.
 hipError_t launch_conv(const ConvArgs& a, hipStream_t s);
 // Split the channel sum of this shape?  Returns 1, 2 or 4 (host heuristic: few tiles, many chunks).
-int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo);
+int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo, bool unit_stride);
 
 struct ReduceArgs {       // out[r] = reduce over `cols` contiguous values
   const void* in;

@@ -165,9 +165,12 @@ hipError_t launch_conv3_i8_t0(const ConvArgs&, const ConvGeom&, hipStream_t);
 hipError_t launch_conv3_i8_t1(const ConvArgs&, const ConvGeom&, hipStream_t);
 hipError_t launch_conv3_i8_t2(const ConvArgs&, const ConvGeom&, hipStream_t);
 
-// 64 x 256 tiles while they number at least three quarters of the compute units.
-static bool conv_prefers_wide_tile(int64_t M, int O) {
-  return ceil_div(M, 256) * ceil_div(O, 64) >= 192;
+// 64 x 256 tiles while they number at least three quarters of the compute units, or, for unit
+// strides, when halving each tile's channel sum (nchunk chunks; the split needs a multiple of 8)
+// gets them there.  (With larger strides a 256-position patch is too large a load per chunk.)
+static bool conv_prefers_wide_tile(int64_t M, int O, int nchunk, bool unit_stride) {
+  const int64_t tiles = ceil_div(M, 256) * ceil_div(O, 64);
+  return tiles >= 192 || (unit_stride && nchunk % 8 == 0 && tiles * 2 >= 192 && tiles * 2 <= 256);
 }
 
 template <typename TR>
@@ -180,7 +183,7 @@ static hipError_t launch_conv3(const ConvArgs& a, const ConvGeom& g, hipStream_t
   auto t1 = [&]() { return i8 ? launch_conv3_i8_t1(a, g, s) : launch_conv3_bf16_t1(a, g, s); };
   auto t2 = [&]() { return i8 ? launch_conv3_i8_t2(a, g, s) : launch_conv3_bf16_t2(a, g, s); };
   hipError_t e = hipErrorInvalidValue;
-  const bool wide = conv_prefers_wide_tile(g.M, a.O);
+  const bool wide = conv_prefers_wide_tile(g.M, a.O, a.Cpad / (32 / TR::kEsz), a.Sh * a.Sw == 1);
   e = wide ? t1() : t2();
   if (e != hipErrorInvalidValue) return e;
   e = wide ? t2() : t1();
@@ -202,10 +205,53 @@ conv_splitk_finish_kernel(const AccT* __restrict__ partial, int ksplit, int64_t 
   }
 }
 
-int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo) {
+// Same, four results per thread; total and all pointers are multiples of four elements.
+template <typename AccT>
+__global__ void __launch_bounds__(256)
+conv_splitk_finish_vec_kernel(const AccT* __restrict__ partial, int ksplit, int64_t total,
+                              const void* __restrict__ residual, void* __restrict__ out, int out_dtype,
+                              int relu) {
+  typedef AccT acc4_t __attribute__((ext_vector_type(4)));
+  const int64_t nvec = total / 4;
+  for (int64_t q = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; q < nvec;
+       q += int64_t(gridDim.x) * blockDim.x) {
+    acc4_t v = __builtin_nontemporal_load(reinterpret_cast<const acc4_t*>(partial) + q);
+    for (int k = 1; k < ksplit; ++k)
+      v += __builtin_nontemporal_load(reinterpret_cast<const acc4_t*>(partial + int64_t(k) * total) + q);
+    if constexpr (__is_same(AccT, int32_t)) {
+      if (residual) v += reinterpret_cast<const acc4_t*>(residual)[q];
+      if (relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = v[e] > 0 ? v[e] : 0;
+      }
+      reinterpret_cast<acc4_t*>(out)[q] = v;
+    } else if (out_dtype == GS_F32) {
+      if (residual) v += reinterpret_cast<const acc4_t*>(residual)[q];
+      if (relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+      }
+      reinterpret_cast<acc4_t*>(out)[q] = v;
+    } else {
+      if (residual) {
+        const i32x2 r = reinterpret_cast<const i32x2*>(residual)[q];
+        v[0] += __uint_as_float(uint32_t(r.x) << 16); v[1] += __uint_as_float(uint32_t(r.x) & 0xffff0000u);
+        v[2] += __uint_as_float(uint32_t(r.y) << 16); v[3] += __uint_as_float(uint32_t(r.y) & 0xffff0000u);
+      }
+      if (relu) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+      }
+      const i32x2 w = {int32_t(pack_bf16x2(v[0], v[1])), int32_t(pack_bf16x2(v[2], v[3]))};
+      reinterpret_cast<i32x2*>(out)[q] = w;
+    }
+  }
+}
+
+int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo, bool unit_stride) {
   const int64_t M = int64_t(N) * Ho * Wo;
-  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O) ? 256 : 128) * ceil_div(O, 64);
   const int nchunk = conv_cpad(in_dtype, C) / (in_dtype == GS_I8 ? 32 : 16);
+  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O, nchunk, unit_stride) ? 256 : 128) * ceil_div(O, 64);
   const int cus = 256;
   if (tiles * 4 <= cus && nchunk % 16 == 0) return 4;
   if (tiles * 2 <= cus && nchunk % 8 == 0) return 2;
@@ -241,10 +287,20 @@ static hipError_t launch_conv_t(const ConvArgs& a_in, hipStream_t s) {
     if (e == hipSuccess) {
       using AccT = typename TR::acc_t;
       const int64_t total = g.M * a.O;
-      const int64_t b = ceil_div(total, 256);
-      hipLaunchKernelGGL((conv_splitk_finish_kernel<AccT>), dim3(unsigned(b < 4096 ? b : 4096)), dim3(256), 0,
-                         s, static_cast<const AccT*>(a.partial), a.ksplit, total, a.residual, a.out,
-                         a.out_dtype, a.relu);
+      const size_t osz = dtype_size(a.out_dtype);
+      const bool vec = total % 4 == 0 && reinterpret_cast<uintptr_t>(a.partial) % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(a.out) % (4 * osz) == 0 &&
+                       reinterpret_cast<uintptr_t>(a.residual) % (4 * osz) == 0;
+      const int64_t b = ceil_div(vec ? total / 4 : total, 256);
+      const dim3 grid(unsigned(b < 4096 ? b : 4096));
+      if (vec)
+        hipLaunchKernelGGL((conv_splitk_finish_vec_kernel<AccT>), grid, dim3(256), 0, s,
+                           static_cast<const AccT*>(a.partial), a.ksplit, total, a.residual, a.out,
+                           a.out_dtype, a.relu);
+      else
+        hipLaunchKernelGGL((conv_splitk_finish_kernel<AccT>), grid, dim3(256), 0, s,
+                           static_cast<const AccT*>(a.partial), a.ksplit, total, a.residual, a.out,
+                           a.out_dtype, a.relu);
       return hipGetLastError();
     }
     if (e != hipErrorInvalidValue) return e;
