@@ -46,7 +46,7 @@ static hipError_t launch_conv4_ring(const ConvArgs& a, const ConvGeom& g, size_t
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  const int64_t tiles = ceil_div(g.M, TP) * ceil_div(a.O, TO) * (a.ksplit > 1 ? a.ksplit : 1);
+  const int64_t tiles = ceil_div(g.M, g.tps) * ceil_div(a.O, TO) * (a.ksplit > 1 ? a.ksplit : 1);
   const int64_t grid = tiles < conv_num_cus() ? tiles : conv_num_cus();
   hipLaunchKernelGGL(kern, dim3(unsigned(grid)), dim3(512), lds_bytes, s, a, g);
   return hipGetLastError();
@@ -74,7 +74,20 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   const int ksplit = a.ksplit > 1 ? a.ksplit : 1;
   const int nchunk = a.Cpad / (32 / TR::kEsz);
   if (nchunk % (2 * ksplit) != 0) return hipErrorInvalidValue;   // the ring holds two or four chunks
-  g.max_rows = conv_max_rows(a, g.M, g.HWo, TP);
+  // Positions per tile: TP, or fewer (in steps that keep each wave's share a multiple of 4) when
+  // that lowers rounds x tile cost, a tile's cost being half fixed (the MFMA blocks stay TP wide)
+  // and half proportional to its positions (patch traffic, write-back).  Only where that
+  // proportional part matters: strided windows (a patch of Sh*Sw pixels per position) and tiles
+  // of at most four channel chunks; elsewhere the MFMA phases bound a tile and narrower tiles
+  // measured slower.
+  g.tps = TP;
+  if (a.Sh * a.Sw > 1 || nchunk / ksplit <= 4) {
+    const int64_t per_m = ceil_div(a.O, TO) * ksplit, cus = conv_num_cus();
+    auto cost = [&](int tps) { return ceil_div(ceil_div(g.M, tps) * per_m, cus) * (TP + tps); };
+    for (int tps = TP - 4 * WP; tps >= TP / 2; tps -= 4 * WP)
+      if (cost(tps) < cost(g.tps)) g.tps = tps;
+  }
+  g.max_rows = conv_max_rows(a, g.M, g.HWo, g.tps);
   if (g.max_rows < 0) return hipErrorInvalidValue;
   const size_t stage_bytes = 4 * 32 * size_t(TP / WP * 4 + 16);   // epilogue staging, one region per wave
   const size_t patch_bytes = 2 * size_t(g.max_rows) * g.PW * 48;
@@ -88,7 +101,7 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   auto items = [&](int vw) { return int64_t(g.max_rows) * (a.W / vw) * 2; };
   // Every segment of a tile (one per image it touches) may end with a partial flat item per
   // channel group.
-  const int64_t segs = (TP + g.HWo - 2) / g.HWo + 1;
+  const int64_t segs = (g.tps + g.HWo - 2) / g.HWo + 1;
   auto flat_items = [&](int vw) { return 2 * ((int64_t(g.max_rows) * a.W + vw - 1) / vw + segs); };
 #define GS_TRY(VW_, MAXI_)                                                                   \
   if (a.W % VW_ == 0 && items(VW_) <= 256 * MAXI_)                                          \

@@ -87,7 +87,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool producer = wave >= 4;
   const int M = int(g.M);
-  const int tiles_m = (M + TP - 1) / TP;
+  // A tile covers g.tps <= TP positions, g.tps / WP per consumer wave column (a multiple of 4);
+  // the MFMA blocks are TP wide and the columns past a wave's share are computed on a valid
+  // stand-in position and dropped.  The host shrinks tiles when that fills more compute units.
+  const int tps = g.tps, wpv = tps / WP;
+  const int tiles_m = (M + tps - 1) / tps;
   // A work item ("tile" below) is (position tile, channel tile, K split): the split index runs
   // fastest so that workgroups launched together share a patch.
   const int ksplit = a.ksplit, kshift = ksplit == 4 ? 2 : ksplit == 2 ? 1 : 0;
@@ -115,9 +119,9 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   auto tile_range = [&](int item, int* m0, int* mend, int* o0) {
     const int tile = lg(item) >> kshift;
     const int to = int(dTiles.div(uint32_t(tile)));
-    *m0 = (tile - to * tiles_m) * TP;
+    *m0 = (tile - to * tiles_m) * tps;
     *o0 = to * TO;
-    *mend = *m0 + TP < M ? *m0 + TP : M;
+    *mend = *m0 + tps < M ? *m0 + tps : M;
   };
 
   int tile = blockIdx.x;
@@ -411,8 +415,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     bool pos_ok[NJ];
 #pragma unroll
     for (int n = 0; n < NJ; ++n) {
-      const int m = m0 + wp * WPT + n * 32 + (lane & 31);
-      pos_ok[n] = m < M;
+      const int m = m0 + wp * wpv + n * 32 + (lane & 31);
+      pos_ok[n] = n * 32 + (lane & 31) < wpv && m < M;
       pbase[n] = (lane >> 5) * 16;
       out_base[n] = 0;
       if (pos_ok[n]) {
@@ -444,8 +448,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     constexpr int NIT = 32 / ROWS_PER_IT;            // write-back steps per 32-channel block
     uint8_t* stage = sl + wave * (32 * RS);
     const int gq = lane % GR, rsub = lane / GR;
-    const int mm = m0 + wp * WPT + gq * 4;
-    const bool grp_ok = mm < M;
+    const int mm = m0 + wp * wpv + gq * 4;
+    const bool grp_ok = gq * 4 < wpv && mm < M;
     const int gimg = int(g.dHWo.div(uint32_t(grp_ok ? mm : 0)));
     const uint32_t gbase = uint32_t(gimg) * uint32_t(a.O) * uint32_t(g.HWo) + uint32_t(mm - gimg * g.HWo);
     // Destination: the output, or with a split channel sum this split's slice of the partials

@@ -36,6 +36,7 @@ struct ConvGeom {
   int64_t M;        // N * Ho * Wo
   int max_rows;     // most patch rows any tile needs
   int pair_ok;      // W even: pixel pairs may be loaded with one access
+  int tps;          // producer/consumer kernel: positions a tile covers (<= its MFMA width TP)
   FastDiv dHWo, dWo;  // division by Ho*Wo and by Wo
 };
 
