@@ -102,7 +102,7 @@ class Conv3x3:
     """ResNet-style 3x3 convolution: N=32, C=64, 56x56 -> 64 channels, stride 1, pad 1, bf16."""
 
     name = "resnet-style 3x3 conv N=32 C=64 H=W=56 O=64 s1 p1, bf16 in/out, fp32 accumulate"
-    dominant = "conv_direct3_kernel"
+    dominant = "conv_direct4_kernel"
 
     def __init__(self, dev):
         from paper_2105_09377_amd import binding as gs, synth
