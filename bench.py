@@ -154,9 +154,9 @@ class Conv3x3Batch64(Conv3x3):
 
 
 class ResNet18:
-    """ResNet-18-shaped stack forward at batch 64 (the largest of the five workloads): stem
-    convolution as im2col + dense contraction, max pooling, sixteen 3x3 and three 1x1 convolutions
-    with fused residual / ReLU, global average, classifier."""
+    """ResNet-18-shaped stack forward at batch 64 (the largest of the five workloads): 7x7 stem
+    convolution, max pooling, sixteen 3x3 convolutions (direct form) and three 1x1 stride-2
+    projections (im2col form) with fused residual / ReLU, global average, classifier."""
 
     name = "resnet18-shaped conv stack forward, batch 64, 3x224x224, bf16 in/out, fp32 accumulate"
     dominant = "conv_direct4_kernel (stage 1: N=64 C=64 56x56 -> 64, 3x3 s1 p1; 4 of the 20 convolutions)"
