@@ -11,6 +11,17 @@
 // k -> LDS offset, run the MFMAs (wave w: positions 32 (w % 4) .. + 31 against channels 32 (w / 4) .. + 31), and
 // write the results through a per-wave LDS staging area as 8- or 16-byte stores with residual add
 // and ReLU fused.  The weight tile of 64 output channels is loaded once per workgroup.
+//
+// Row-window form (DR).  When a window row is at most 16 bytes (Kw <= 8 bf16 / 16 int8) and
+// consecutive windows start a whole number of dwords apart (Sw * element size a multiple of 4),
+// the contraction index is laid out as (c, dx, dy padded to 16 bytes): the 16 bytes an MFMA lane
+// needs for position y and row (c, dx) are then the 16 bytes of the staged input row starting at
+// column y*Sw - Pw, so the B fragments are read straight from the staged rows with the columns
+// past Kw masked to zero, and no [position][k] tile is formed at all.  The first data column of a
+// staged row is Pw, which puts every window on a dword boundary (16-byte LDS reads off a dword
+// boundary are several times slower); the staged data may then sit off a dword boundary and is
+// written with stores aligned to the element only, which the hardware's unaligned mode allows
+// and which are few.  The weights get a second copy in that order, zero in the padding.
 #include "common.h"
 
 #include <limits.h>
@@ -27,13 +38,14 @@ struct SmallCArgs {
   int otiles;       // 64-channel tiles
   int64_t tasks;    // N * Ho * xtiles * otiles
   int vec_ok;       // input rows are whole 16-byte vectors
+  uint32_t dr_mask[4];   // row-window form: keeps the first Kw elements of a 16-byte window
   FastDiv dvpr, dW, dhalo, dKh, dT, dKw, dchunk;
 };
 
 constexpr int kSmallCBatch = 4;   // 16-byte vectors a thread stages per task
 constexpr int kSmallCThreads = 512;
 
-template <typename TR>
+template <typename TR, bool DR>
 __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs p) {
   constexpr int NT = kSmallCThreads;
   using T = typename std::conditional<TR::kEsz == 1, uint8_t, uint16_t>::type;
@@ -82,7 +94,7 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
     stage[int(r) * p.pitch + (int(h) < p.XO ? int(h) : a.W + int(h))] = T(0);
   }
   for (int id = tid; id < p.pitch; id += NT) stage[zero_row + id] = T(0);
-  for (int k = tid; k < p.Kp; k += NT) {
+  for (int k = tid; !DR && k < p.Kp; k += NT) {
     int off = zero_row;
     if (k < p.K) {
       uint32_t c, t, dx, dy;
@@ -139,8 +151,9 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
         if (u * NT < nvec && id < nvec) {
           uint32_t r, v;
           p.dvpr.divmod(uint32_t(id), &r, &v);
-          int32_t* d = reinterpret_cast<int32_t*>(reinterpret_cast<uint8_t*>(stage) +
-                                                  (int(r) * p.pitch + p.XO) * ESZ + int(v) * 16);
+          typedef int32_t word_t __attribute__((aligned(1)));   // aligned to the element only
+          word_t* d = reinterpret_cast<word_t*>(reinterpret_cast<uint8_t*>(stage) +
+                                                (int(r) * p.pitch + p.XO) * ESZ + int(v) * 16);
           d[0] = val[u][0];
           d[1] = val[u][1];
           d[2] = val[u][2];
@@ -160,7 +173,7 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
     __syncthreads();
     if (vec_ok && task + gridDim.x < p.tasks) issue_loads(task + gridDim.x);
     // -- gather the [position][k] tile: item = (position, 16-byte chunk of k)
-    {
+    if constexpr (!DR) {
       const int nchunk = p.Kp / EPV;
       const int items = npos * nchunk;
       for (int id = tid; id < items; id += NT) {
@@ -175,8 +188,8 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
           v[i] = *reinterpret_cast<const T*>(reinterpret_cast<const uint8_t*>(stage) + offs[i] + shift);
         *reinterpret_cast<outv_t*>(tl + int(pos) * p.wpb + int(j) * 16) = v;
       }
+      __syncthreads();
     }
-    __syncthreads();
     // -- multiply: wave w owns positions 32 (w % 4) .. + 31 and channels 32 (w / 4) .. + 31
     const int pb_ = wave & 3, ob_ = wave >> 2;
     typename TR::accv_t acc;
@@ -184,15 +197,31 @@ __global__ void __launch_bounds__(kSmallCThreads) conv_smallc_kernel(SmallCArgs 
     for (int v = 0; v < 16; ++v) acc[v] = 0;
     if (pb_ * 32 < npos) {
       const uint8_t* ap = wl + (ob_ * 32 + (lane & 31)) * p.wpb + (lane >> 5) * 16;
-      const uint8_t* bp = tl + (pb_ * 32 + (lane & 31)) * p.wpb + (lane >> 5) * 16;
       const int ksteps = p.Kp * ESZ / 32;
-      for (int ks = 0; ks < ksteps; ++ks) {
-        const i32x4 b = *reinterpret_cast<const i32x4*>(bp + ks * 32);
-        const i32x4 a0 = *reinterpret_cast<const i32x4*>(ap + ks * 32);
-        acc = TR::mfma(a0, b, acc);
+      if constexpr (DR) {
+        // K step ks holds input rows 2 ks and 2 ks + 1 (the row after the last is the zero row);
+        // lanes past the last position read the last position's windows and are not stored.
+        typedef i32x4 win_t __attribute__((aligned(4)));   // windows start on dword boundaries
+        const int pos = pb_ * 32 + (lane & 31);
+        const uint8_t* bp = reinterpret_cast<const uint8_t*>(stage) +
+                            (p.XO - a.Pw + (y0 + (pos < npos ? pos : npos - 1)) * a.Sw) * ESZ +
+                            (lane >> 5) * row_bytes;
+        const i32x4 keep = {int(p.dr_mask[0]), int(p.dr_mask[1]), int(p.dr_mask[2]), int(p.dr_mask[3])};
+        for (int ks = 0; ks < ksteps; ++ks) {
+          const i32x4 b = *reinterpret_cast<const win_t*>(bp + ks * 2 * row_bytes) & keep;
+          const i32x4 a0 = *reinterpret_cast<const i32x4*>(ap + ks * 32);
+          acc = TR::mfma(a0, b, acc);
+        }
+      } else {
+        const uint8_t* bp = tl + (pb_ * 32 + (lane & 31)) * p.wpb + (lane >> 5) * 16;
+        for (int ks = 0; ks < ksteps; ++ks) {
+          const i32x4 b = *reinterpret_cast<const i32x4*>(bp + ks * 32);
+          const i32x4 a0 = *reinterpret_cast<const i32x4*>(ap + ks * 32);
+          acc = TR::mfma(a0, b, acc);
+        }
       }
     }
-    __syncthreads();                                   // the tile is free: it becomes the staging areas
+    if constexpr (!DR) __syncthreads();                // the tile is free: it becomes the staging areas
     // -- epilogue: out[((n*O + o)*Ho + ho)*Wo + y]
     if (pb_ * 32 < npos) {
       uint8_t* st = tl + wave * (32 * RS);
@@ -282,6 +311,24 @@ conv_smallc_pack_kernel(const T* __restrict__ w, T* __restrict__ wn, int O, int 
   }
 }
 
+// Row-window copy: ((O rounded up to 64),(C*Kh rounded up to 2, 16 bytes)): element dy of row
+// r = c*Kh + dx is w[o][c][dx][dy], zeros for dy >= Kw and in the padding row.
+template <typename T>
+__global__ void __launch_bounds__(256)
+conv_smallc_pack_rows_kernel(const T* __restrict__ w, T* __restrict__ wn, int O, int nrows, int Kw,
+                             int rows2, int O64) {
+  constexpr int G = 16 / int(sizeof(T));
+  const int64_t total = int64_t(O64) * rows2 * G;
+  for (int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; f < total;
+       f += int64_t(gridDim.x) * blockDim.x) {
+    const int dy = int(f % G);
+    const int64_t t = f / G;
+    const int r = int(t % rows2);
+    const int64_t o = t / rows2;
+    wn[f] = (o < O && r < nrows && dy < Kw) ? w[(o * nrows + r) * Kw + dy] : T(0);
+  }
+}
+
 static int smallc_kp(int in_dtype, int C, int Kh, int Kw) {
   const int per = in_dtype == GS_I8 ? 32 : 16;
   return int(round_up(int64_t(C) * Kh * Kw, per));
@@ -289,9 +336,20 @@ static int smallc_kp(int in_dtype, int C, int Kh, int Kw) {
 
 bool conv_is_smallc(int in_dtype, int C) { return C * int(dtype_size(in_dtype)) < 32 && C > 0; }
 
+// The row-window copy exists when a window row fits 16 bytes (whether it is used depends on the
+// stride, which the packing call does not know).
+static bool smallc_has_rows_copy(int in_dtype, int Kw) { return Kw * int(dtype_size(in_dtype)) <= 16; }
+static size_t smallc_natural_bytes(int in_dtype, int O, int C, int Kh, int Kw) {
+  return size_t(round_up(O, 64)) * smallc_kp(in_dtype, C, Kh, Kw) * dtype_size(in_dtype);
+}
+static size_t smallc_rows_offset(int in_dtype, int O, int C, int Kh, int Kw) {
+  return size_t(round_up(int64_t(smallc_natural_bytes(in_dtype, O, C, Kh, Kw)), 256));
+}
+
 size_t conv_smallc_weight_bytes(int in_dtype, int O, int C, int Kh, int Kw) {
   if (!conv_is_smallc(in_dtype, C)) return 0;
-  return size_t(round_up(O, 64)) * smallc_kp(in_dtype, C, Kh, Kw) * dtype_size(in_dtype);
+  if (!smallc_has_rows_copy(in_dtype, Kw)) return smallc_natural_bytes(in_dtype, O, C, Kh, Kw);
+  return smallc_rows_offset(in_dtype, O, C, Kh, Kw) + size_t(round_up(O, 64)) * round_up(C * Kh, 2) * 16;
 }
 
 hipError_t launch_conv_smallc_pack(const void* w, void* wn, int in_dtype, int O, int C, int Kh, int Kw,
@@ -307,6 +365,18 @@ hipError_t launch_conv_smallc_pack(const void* w, void* wn, int in_dtype, int O,
   else
     hipLaunchKernelGGL((conv_smallc_pack_kernel<uint16_t>), grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wn), O, K, Kp, O64);
+  if (smallc_has_rows_copy(in_dtype, Kw)) {
+    const int nrows = C * Kh, rows2 = int(round_up(nrows, 2));
+    void* wrows = static_cast<uint8_t*>(wn) + smallc_rows_offset(in_dtype, O, C, Kh, Kw);
+    const int64_t b2 = ceil_div(int64_t(O64) * rows2 * 16 / int64_t(dtype_size(in_dtype)), 256);
+    const dim3 grid2(unsigned(b2 < 4096 ? b2 : 4096));
+    if (in_dtype == GS_I8)
+      hipLaunchKernelGGL((conv_smallc_pack_rows_kernel<uint8_t>), grid2, dim3(256), 0, s,
+                         static_cast<const uint8_t*>(w), static_cast<uint8_t*>(wrows), O, nrows, Kw, rows2, O64);
+    else
+      hipLaunchKernelGGL((conv_smallc_pack_rows_kernel<uint16_t>), grid2, dim3(256), 0, s,
+                         static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wrows), O, nrows, Kw, rows2, O64);
+  }
   return hipGetLastError();
 }
 
@@ -332,8 +402,22 @@ static hipError_t launch_smallc_t(const ConvArgs& a, hipStream_t s) {
   p.c = a;
   p.K = a.C * a.Kh * a.Kw;
   p.Kp = smallc_kp(a.in_dtype, a.C, a.Kh, a.Kw);
+  // Row-window form: windows a whole number of dwords apart, a window row within 16 bytes.
+  const bool dr = smallc_has_rows_copy(a.in_dtype, a.Kw) && (a.Sw * ESZ) % 4 == 0;
+  if (dr) {
+    p.Kp = int(round_up(a.C * a.Kh, 2)) * EPV;
+    p.c.wr = static_cast<const uint8_t*>(a.wr) + smallc_rows_offset(a.in_dtype, a.O, a.C, a.Kh, a.Kw);
+    for (int d = 0; d < 4; ++d) {
+      uint32_t m = 0;
+      for (int e = 0; e < EPD; ++e)
+        if (d * EPD + e < a.Kw) m |= (ESZ == 2 ? 0xffffu : 0xffu) << (e * ESZ * 8);
+      p.dr_mask[d] = m;
+    }
+  }
   p.wpb = p.Kp * ESZ + 16;
-  p.XO = int(round_up(a.Pw, EPD));
+  // First data column of a staged row.  Row-window form: exactly Pw, so that window y starts
+  // y*Sw elements into the row, on a dword boundary (the staged data itself may then sit off one).
+  p.XO = dr ? a.Pw : int(round_up(a.Pw, EPD));
   const int64_t reach = int64_t(p.XO) - a.Pw + int64_t(a.Wo - 1) * a.Sw + a.Kw;
   const int64_t width = reach > p.XO + a.W ? reach : p.XO + a.W;
   p.pitch = int(round_up(width, EPD));
@@ -343,7 +427,7 @@ static hipError_t launch_smallc_t(const ConvArgs& a, hipStream_t s) {
               int64_t(nrows) * (a.W * ESZ / 16) <= kSmallCThreads * kSmallCBatch) ? 1 : 0;
   const int64_t stage_bytes = round_up(int64_t(nrows + 1) * p.pitch * ESZ, 16);
   constexpr int kStaging = (kSmallCThreads / 64) * 32 * (32 * 4 + 16);   // one staging area per wave
-  p.tile_bytes = 128 * p.wpb > kStaging ? 128 * p.wpb : kStaging;
+  p.tile_bytes = (!dr && 128 * p.wpb > kStaging) ? 128 * p.wpb : kStaging;
   const int64_t lds_bytes = 64 * int64_t(p.wpb) + p.tile_bytes + stage_bytes + int64_t(p.Kp) * 4;
   if (lds_bytes > 96 * 1024 || (int64_t(nrows) + 1) * p.pitch * ESZ > (1 << 20)) return hipErrorInvalidValue;
   p.xtiles = int(ceil_div(a.Wo, 128));
@@ -358,13 +442,13 @@ static hipError_t launch_smallc_t(const ConvArgs& a, hipStream_t s) {
   p.dT = FastDiv::make(uint32_t(a.Kh * a.Kw));
   p.dKw = FastDiv::make(uint32_t(a.Kw));
   p.dchunk = FastDiv::make(uint32_t(p.Kp / EPV));
-  auto kern = conv_smallc_kernel<TR>;
-  static bool attr_done = false;
-  if (!attr_done) {
+  auto kern = dr ? conv_smallc_kernel<TR, true> : conv_smallc_kernel<TR, false>;
+  static bool attr_done[2] = {false, false};
+  if (!attr_done[dr]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done[dr] = true;
   }
   int per_cu = int((160 * 1024) / (lds_bytes + 512));
   per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;

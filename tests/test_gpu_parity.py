@@ -163,6 +163,11 @@ CONV_CASES = [
     ("bf16", 2, 8, 16, 16, 64, 3, 3, (1, 1), (1, 1), torch.bfloat16),
     ("i8", 2, 16, 12, 32, 33, 3, 3, (1, 2), (1, 1), torch.int32),
     ("i8", 1, 3, 9, 9, 4, 1, 1, (1, 1), (0, 0), torch.int32),
+    # few channels, windows a whole number of dwords apart: fragments read straight from the staged rows
+    ("bf16", 2, 3, 33, 37, 20, 5, 8, (1, 2), (2, 3), torch.float32),     # 8-wide kernel rows
+    ("bf16", 1, 2, 20, 300, 70, 3, 3, (2, 2), (1, 1), torch.bfloat16),   # Wo = 150, two channel tiles
+    ("i8", 2, 4, 16, 40, 33, 3, 5, (1, 4), (1, 2), torch.int32),
+    ("bf16", 3, 1, 9, 9, 4, 1, 1, (2, 2), (0, 0), torch.float32),
     # few output tiles, many chunks: the channel sum is split among workgroups (2 and 4 ways)
     ("bf16", 2, 256, 7, 7, 128, 3, 3, (1, 1), (1, 1), torch.bfloat16),
     ("bf16", 3, 128, 8, 8, 96, 3, 3, (1, 1), (1, 1), torch.float32),
