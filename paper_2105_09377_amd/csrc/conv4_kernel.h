@@ -4,7 +4,8 @@
 // waves, two per SIMD, with fixed roles:
 //   * waves 0-3, the consumers, only read MFMA fragments from LDS, multiply, and write results;
 //   * waves 4-7, the producers, only move data: activation rows global -> registers (a ring two
-//     chunks deep) -> transposed 16-byte LDS writes, and weight slabs global -> LDS directly.
+//     or four chunks deep) -> transposed 16-byte LDS writes, and weight slabs global -> LDS
+//     directly.
 // A SIMD therefore always has a wave with MFMAs to issue next to a wave doing address, packing
 // and memory work, and the hardware interleaves them; with four do-everything waves those phases
 // ran one after the other.  One workgroup barrier per channel chunk hands a filled patch / weight
@@ -12,6 +13,10 @@
 // tile boundaries without a gap (chunk 0 of the next tile is stored during the last chunk of this
 // one), so the consumers' epilogue overlaps the producers' work for the next tile; the epilogue
 // stages results in an LDS region of its own for that reason.
+//
+// Work items (position tile, channel tile, split of the channel sum) are dealt so that each XCD
+// owns a contiguous range of them; a tile may cover fewer positions than its MFMA width (g.tps);
+// producer items are VW pixels of a row or, in the FLAT form, VW pixels consecutive in memory.
 #pragma once
 #include "conv_kernels.h"
 
