@@ -45,9 +45,9 @@ KERNEL_SOURCES = {
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (27.06e6 + 25.70e6, "conv", "6f73c072134f45ea644a464ae85f6cafca07d4044598382fcd846f4f1acb147b"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
-    "conv3x3": (14.21e6 + 12.85e6, "conv", "6f73c072134f45ea644a464ae85f6cafca07d4044598382fcd846f4f1acb147b"),
-    "conv3x3_b64": (27.06e6 + 25.70e6, "conv", "6f73c072134f45ea644a464ae85f6cafca07d4044598382fcd846f4f1acb147b"),
+    "resnet18": (27.06e6 + 25.70e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
+    "conv3x3": (14.21e6 + 12.85e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),
+    "conv3x3_b64": (27.06e6 + 25.70e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),
     "im2col_gather": (12.97e6 + 115.65e6, "windows", "6ab63993fd0789bc760165f2af88d90a47cd8eb668fe1f07ef0387bf9e5ff547"),
     "maxpool": (103.00e6 + 25.69e6, "reduce", "686a3bcee0a83d48777d8333106581c15ca4b340a9dc4ac1c67f7d0a1cffeb71"),
     "reduce": (268.43e6 + 0.52e6, "reduce", "686a3bcee0a83d48777d8333106581c15ca4b340a9dc4ac1c67f7d0a1cffeb71"),
