@@ -103,6 +103,35 @@ reduce_rows_vec_kernel(const T* __restrict__ in, void* __restrict__ out, int out
   }
 }
 
+// Short rows of any length and alignment (a 7x7 plane averaged to one value): the rows are
+// contiguous in memory, so a workgroup copies its 128 rows to LDS with aligned 16-byte loads,
+// whatever the row length, and two threads then fold each row from LDS.
+constexpr int kShortRows = 128;   // rows per workgroup: 128 * cols * sizeof(T) is a multiple of 16
+template <typename T>
+__global__ void __launch_bounds__(256)
+reduce_rows_short_kernel(const T* __restrict__ in, void* __restrict__ out, int out_dtype, int op,
+                         int64_t rows, int cols, float scale) {
+  using A = typename Elem<T>::acc;
+  constexpr int EPV = 16 / int(sizeof(T));
+  extern __shared__ __attribute__((aligned(16))) uint8_t short_lds[];
+  T* buf = reinterpret_cast<T*>(short_lds);
+  const int64_t row0 = int64_t(blockIdx.x) * kShortRows;
+  const int nrows = int(rows - row0 < kShortRows ? rows - row0 : kShortRows);
+  const int nelem = nrows * cols;
+  const T* src = in + row0 * cols;                 // 16-byte aligned: row0 is a multiple of 128
+  const int nvec = nelem / EPV;                    // whole vectors inside this workgroup's rows
+  for (int v = threadIdx.x; v < nvec; v += 256)
+    reinterpret_cast<i32x4*>(buf)[v] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(src) + v);
+  for (int e = nvec * EPV + threadIdx.x; e < nelem; e += 256) buf[e] = src[e];
+  __syncthreads();
+  const int r = threadIdx.x >> 1, half = threadIdx.x & 1;
+  A acc = ident<A>(op);
+  if (r < nrows)
+    for (int c = half; c < cols; c += 2) acc = combine(acc, Elem<T>::load(buf, int64_t(r) * cols + c), op);
+  acc = combine(acc, __shfl_xor(acc, 1, 2), op);
+  if (r < nrows && half == 0) store_out<A>(out, out_dtype, row0 + r, finish(acc, scale));
+}
+
 // One workgroup of 256 threads per row, for long rows.
 template <typename T>
 __global__ void __launch_bounds__(256)
@@ -161,6 +190,12 @@ static hipError_t launch_reduce_t(const ReduceArgs& a, hipStream_t s) {
     else if (nv <= 32) GS_LAUNCH_VEC(32)
     else GS_LAUNCH_VEC(64)
 #undef GS_LAUNCH_VEC
+    return hipGetLastError();
+  }
+  if (a.cols > 8 && a.cols < 8 * EPV && a.rows >= 4 * kShortRows && reinterpret_cast<uintptr_t>(a.in) % 16 == 0) {
+    const size_t lds = size_t(round_up(int64_t(kShortRows) * a.cols * int64_t(sizeof(T)), 16));
+    hipLaunchKernelGGL((reduce_rows_short_kernel<T>), dim3(unsigned(ceil_div(a.rows, kShortRows))), dim3(256),
+                       lds, s, in, a.out, a.out_dtype, a.op, a.rows, int(a.cols), a.scale);
     return hipGetLastError();
   }
   if (a.cols <= 1) GS_LAUNCH_GROUP(1);

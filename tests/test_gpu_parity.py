@@ -287,6 +287,9 @@ REDUCE_CASES = [
     ("i8", (7, 13), 1), ("i8", (3, 5, 4), 1), ("i32", (10, 49), 1), ("bf16", (6, 5, 7, 7), 2),
     ("f32", (33, 100), 1), ("bf16", (3, 5000), 1), ("f32", (1000, 1), 1), ("i32", (2, 9000), 1),
     ("bf16", (513, 4), 1), ("f32", (5,), 0),
+    # many short rows: staged through LDS, 128 rows per workgroup, ragged last workgroup
+    ("bf16", (600, 49), 1), ("i8", (777, 33), 1), ("f32", (515, 9), 1), ("i32", (1030, 13), 1),
+    ("bf16", (9, 64, 7, 7), 2),
 ]
 
 
