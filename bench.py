@@ -49,8 +49,8 @@ TRAFFIC = {
     "conv3x3": (14.21e6 + 12.85e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),
     "conv3x3_b64": (27.06e6 + 25.70e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),
     "im2col_gather": (12.97e6 + 115.65e6, "windows", "6ab63993fd0789bc760165f2af88d90a47cd8eb668fe1f07ef0387bf9e5ff547"),
-    "maxpool": (103.00e6 + 25.69e6, "reduce", "686a3bcee0a83d48777d8333106581c15ca4b340a9dc4ac1c67f7d0a1cffeb71"),
-    "reduce": (268.43e6 + 0.52e6, "reduce", "686a3bcee0a83d48777d8333106581c15ca4b340a9dc4ac1c67f7d0a1cffeb71"),
+    "maxpool": (102.99e6 + 25.69e6, "reduce", "82db2f73ebcc5d12f430d500a7f90c3a2157c90f69bbeb327ad69fbd36c16757"),
+    "reduce": (268.44e6 + 0.52e6, "reduce", "82db2f73ebcc5d12f430d500a7f90c3a2157c90f69bbeb327ad69fbd36c16757"),
     "dense": (1634.29e6 + 274.42e6, "gemm", "6215efc06f467af8b959fc0f0ad129d35fc7796084fd7153b0ba22d09f46310a"),
     "mlp_scaled": (29.33e6 + 16.78e6, "gemm", "6215efc06f467af8b959fc0f0ad129d35fc7796084fd7153b0ba22d09f46310a"),
 }
