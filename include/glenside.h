@@ -153,6 +153,25 @@ int glenside_windows_reduce(const gs_ap* in, const int64_t* window, const int64_
 int glenside_pair_reduce(const gs_ap* a, const gs_ap* b, int op, int act, gs_ap* out,
                          void* stream);
 
+/* The Table 1 transformers that move data, materialised (in the other entry points they are folded
+ * into descriptors or into a kernel's addressing).  `out` must be a distinct tensor that already
+ * has the result's dtype, rank, access split and shape; nothing is launched otherwise.
+ *
+ * `transpose` (Table 1; Sec. 4.2; the `(transpose ... (0 3 1 2))` tail of Fig. 5): output dimension
+ * t is input dimension perm[t], over all |S_A| + |S_C| dimensions; the access split stays where it
+ * is.  perm: HOST array of in->rank entries, a permutation.                                        */
+int glenside_transpose(const gs_ap* in, const int64_t* perm, gs_ap* out, void* stream);
+/* `slice` (Table 1; Fig. 7): keeps [lo, hi) of dimension dim.                                      */
+int glenside_slice(const gs_ap* in, int dim, int64_t lo, int64_t hi, gs_ap* out, void* stream);
+/* `concat` (the blocking rewrites of Sec. 5.4, Fig. 6): joins a and b along dim; the other
+ * dimensions, the rank and the access split of a and b agree.                                      */
+int glenside_concat(const gs_ap* a, const gs_ap* b, int dim, gs_ap* out, void* stream);
+/* EXT `pad`: grows dimension dim by lo cells in front and hi behind, filled per gs_pad_mode.       */
+int glenside_pad(const gs_ap* in, int dim, int64_t lo, int64_t hi, int pad_mode, gs_ap* out,
+                 void* stream);
+/* `pair` (Table 1; Sec. 5.4): two patterns of one shape ((a..),(c..)) -> ((a..),(2, c..)).        */
+int glenside_pair(const gs_ap* a, const gs_ap* b, gs_ap* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

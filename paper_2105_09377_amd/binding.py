@@ -32,7 +32,8 @@ EXPORTS = (
     "glenside_cartesian_dot", "glenside_conv2d_direct", "glenside_conv2d_im2col",
     "glenside_conv2d_direct_workspace", "glenside_conv2d_im2col_workspace", "glenside_reduce",
     "glenside_windows_reduce", "glenside_pair_reduce", "glenside_conv2d_pack_weights",
-    "glenside_conv2d_direct_packed",
+    "glenside_conv2d_direct_packed", "glenside_transpose", "glenside_slice", "glenside_concat",
+    "glenside_pad", "glenside_pair",
 )
 
 
@@ -76,6 +77,11 @@ def lib() -> ctypes.CDLL:
         L.glenside_windows_reduce.argtypes = [ap_p, i64_p, i64_p, i64_p, i64_p, ctypes.c_int,
                                               ctypes.c_float, ap_p, vp]
         L.glenside_pair_reduce.argtypes = [ap_p, ap_p, ctypes.c_int, ctypes.c_int, ap_p, vp]
+        L.glenside_transpose.argtypes = [ap_p, i64_p, ap_p, vp]
+        L.glenside_slice.argtypes = [ap_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ap_p, vp]
+        L.glenside_concat.argtypes = [ap_p, ap_p, ctypes.c_int, ap_p, vp]
+        L.glenside_pad.argtypes = [ap_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ap_p, vp]
+        L.glenside_pair.argtypes = [ap_p, ap_p, ap_p, vp]
         _lib = L
     return _lib
 
@@ -277,4 +283,60 @@ def pair_reduce(a: torch.Tensor, b: torch.Tensor, op: int = GS_SUM, act: int = G
     _check(lib().glenside_pair_reduce(ctypes.byref(make_ap(a, a.dim())), ctypes.byref(make_ap(b, b.dim())),
                                       op, act, ctypes.byref(make_ap(out, out.dim())), _stream(a)),
            "pair_reduce")
+    return out
+
+
+def transpose(x: torch.Tensor, n_access: int, perm: Sequence[int],
+              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """transpose (access x n_access) perm, materialised: output dimension t is input dimension perm[t]."""
+    if out is None:
+        out = torch.empty([x.shape[p] for p in perm], dtype=x.dtype, device=x.device)
+    _check(lib().glenside_transpose(ctypes.byref(make_ap(x, n_access)), _i64(perm),
+                                    ctypes.byref(make_ap(out, n_access)), _stream(x)), "transpose")
+    return out
+
+
+def slice_(x: torch.Tensor, n_access: int, dim: int, lo: int, hi: int,
+           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """slice (access x n_access) dim lo hi, materialised."""
+    if out is None:
+        shape = list(x.shape)
+        shape[dim] = hi - lo
+        out = torch.empty(shape, dtype=x.dtype, device=x.device)
+    _check(lib().glenside_slice(ctypes.byref(make_ap(x, n_access)), dim, lo, hi,
+                                ctypes.byref(make_ap(out, n_access)), _stream(x)), "slice")
+    return out
+
+
+def concat(a: torch.Tensor, b: torch.Tensor, n_access: int, dim: int,
+           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """concat a b dim, materialised."""
+    if out is None:
+        shape = list(a.shape)
+        shape[dim] = a.shape[dim] + b.shape[dim]
+        out = torch.empty(shape, dtype=a.dtype, device=a.device)
+    _check(lib().glenside_concat(ctypes.byref(make_ap(a, n_access)), ctypes.byref(make_ap(b, n_access)), dim,
+                                 ctypes.byref(make_ap(out, n_access)), _stream(a)), "concat")
+    return out
+
+
+def pad(x: torch.Tensor, n_access: int, dim: int, lo: int, hi: int, pad_mode: int = GS_PAD_ZERO,
+        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """EXT pad: dimension dim grows by lo cells in front and hi behind."""
+    if out is None:
+        shape = list(x.shape)
+        shape[dim] = x.shape[dim] + lo + hi
+        out = torch.empty(shape, dtype=x.dtype, device=x.device)
+    _check(lib().glenside_pad(ctypes.byref(make_ap(x, n_access)), dim, lo, hi, pad_mode,
+                              ctypes.byref(make_ap(out, n_access)), _stream(x)), "pad")
+    return out
+
+
+def pair(a: torch.Tensor, b: torch.Tensor, n_access: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """pair a b: ((a..),(c..)) x 2 -> ((a..),(2, c..)), materialised."""
+    if out is None:
+        shape = list(a.shape[:n_access]) + [2] + list(a.shape[n_access:])
+        out = torch.empty(shape, dtype=a.dtype, device=a.device)
+    _check(lib().glenside_pair(ctypes.byref(make_ap(a, n_access)), ctypes.byref(make_ap(b, n_access)),
+                               ctypes.byref(make_ap(out, n_access)), _stream(a)), "pair")
     return out

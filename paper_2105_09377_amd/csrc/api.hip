@@ -531,4 +531,169 @@ int glenside_pair_reduce(const gs_ap* a, const gs_ap* b, int op, int act, gs_ap*
   return launch_status(launch_pair_reduce(p, static_cast<hipStream_t>(stream)));
 }
 
+// ---------------------------------------------------------------------------------------------
+// Table 1 transformers that move data
+// ---------------------------------------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+
+void row_major_strides(const gs_ap* a, int64_t* st) {
+  int64_t s = 1;
+  for (int d = a->rank - 1; d >= 0; --d) {
+    st[d] = s;
+    s *= a->shape[d];
+  }
+}
+
+// A box copy between two dense tensors: dims/strides given in the output's dimension order.
+int run_move(const gs_ap* in, gs_ap* out, int rank, const int64_t* dims, const int64_t* is,
+             const int64_t* os, int64_t in_off, int64_t out_off, void* stream) {
+  MoveArgs m;
+  memset(&m, 0, sizeof(m));
+  m.in = in->data;
+  m.out = out->data;
+  m.esz = int(dtype_size(in->dtype));
+  m.rank = rank;
+  for (int d = 0; d < rank; ++d) {
+    m.dims[d] = dims[d];
+    m.is[d] = is[d];
+    m.os[d] = os[d];
+  }
+  m.in_off = in_off;
+  m.out_off = out_off;
+  return launch_status(launch_move(m, static_cast<hipStream_t>(stream)));
+}
+
+int check_result(const gs_ap* out, int dtype, int rank, int n_access, const int64_t* shape) {
+  if (out->dtype != dtype) return GS_ERR_DTYPE;
+  if (out->rank != rank || out->n_access != n_access) return GS_ERR_RANK;
+  for (int d = 0; d < rank; ++d)
+    if (out->shape[d] != shape[d]) return GS_ERR_SHAPE;
+  return GS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int glenside_transpose(const gs_ap* in, const int64_t* perm, gs_ap* out, void* stream) {
+  int st = check_ap(in, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if ((out->data && out->data == in->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (!perm) return GS_ERR_NULL;
+  bool seen[GS_MAX_RANK] = {false};
+  int64_t shape[GS_MAX_RANK], ist[GS_MAX_RANK], is[GS_MAX_RANK], os[GS_MAX_RANK];
+  row_major_strides(in, ist);
+  for (int t = 0; t < in->rank; ++t) {
+    if (perm[t] < 0 || perm[t] >= in->rank || seen[perm[t]]) return GS_ERR_SHAPE;
+    seen[perm[t]] = true;
+    shape[t] = in->shape[perm[t]];
+    is[t] = ist[perm[t]];
+  }
+  st = check_result(out, in->dtype, in->rank, in->n_access, shape);
+  if (st) return st;
+  row_major_strides(out, os);
+  return run_move(in, out, in->rank, shape, is, os, 0, 0, stream);
+}
+
+int glenside_slice(const gs_ap* in, int dim, int64_t lo, int64_t hi, gs_ap* out, void* stream) {
+  int st = check_ap(in, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if ((out->data && out->data == in->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (dim < 0 || dim >= in->rank) return GS_ERR_RANK;
+  if (lo < 0 || lo > hi || hi > in->shape[dim]) return GS_ERR_SHAPE;
+  int64_t shape[GS_MAX_RANK], is[GS_MAX_RANK], os[GS_MAX_RANK];
+  for (int d = 0; d < in->rank; ++d) shape[d] = in->shape[d];
+  shape[dim] = hi - lo;
+  st = check_result(out, in->dtype, in->rank, in->n_access, shape);
+  if (st) return st;
+  row_major_strides(in, is);
+  row_major_strides(out, os);
+  return run_move(in, out, in->rank, shape, is, os, lo * is[dim], 0, stream);
+}
+
+int glenside_concat(const gs_ap* a, const gs_ap* b, int dim, gs_ap* out, void* stream) {
+  int st = check_ap(a, true);
+  if (st) return st;
+  st = check_ap(b, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if ((out->data && out->data == a->data) || (out->data && out->data == b->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (a->rank != b->rank || a->n_access != b->n_access) return GS_ERR_RANK;
+  if (dim < 0 || dim >= a->rank) return GS_ERR_RANK;
+  if (a->dtype != b->dtype) return GS_ERR_DTYPE;
+  int64_t shape[GS_MAX_RANK], as[GS_MAX_RANK], bs[GS_MAX_RANK], os[GS_MAX_RANK];
+  for (int d = 0; d < a->rank; ++d) {
+    if (d != dim && a->shape[d] != b->shape[d]) return GS_ERR_SHAPE;
+    shape[d] = a->shape[d];
+  }
+  shape[dim] = a->shape[dim] + b->shape[dim];
+  st = check_result(out, a->dtype, a->rank, a->n_access, shape);
+  if (st) return st;
+  row_major_strides(a, as);
+  row_major_strides(b, bs);
+  row_major_strides(out, os);
+  st = run_move(a, out, a->rank, a->shape, as, os, 0, 0, stream);
+  if (st) return st;
+  return run_move(b, out, b->rank, b->shape, bs, os, 0, a->shape[dim] * os[dim], stream);
+}
+
+int glenside_pad(const gs_ap* in, int dim, int64_t lo, int64_t hi, int pad_mode, gs_ap* out,
+                 void* stream) {
+  int st = check_ap(in, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if ((out->data && out->data == in->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (dim < 0 || dim >= in->rank) return GS_ERR_RANK;
+  if (lo < 0 || hi < 0) return GS_ERR_SHAPE;
+  if (pad_mode != GS_PAD_ZERO && pad_mode != GS_PAD_LOWEST) return GS_ERR_UNSUPPORTED;
+  int64_t shape[GS_MAX_RANK], is[GS_MAX_RANK], os[GS_MAX_RANK];
+  for (int d = 0; d < in->rank; ++d) shape[d] = in->shape[d];
+  shape[dim] = in->shape[dim] + lo + hi;
+  st = check_result(out, in->dtype, in->rank, in->n_access, shape);
+  if (st) return st;
+  row_major_strides(in, is);
+  row_major_strides(out, os);
+  if (lo + hi > 0) {
+    st = launch_status(launch_fill(out->data, int(dtype_size(in->dtype)), numel(out),
+                                   pad_mode == GS_PAD_LOWEST ? lowest_bits(in->dtype) : 0u,
+                                   static_cast<hipStream_t>(stream)));
+    if (st) return st;
+  }
+  return run_move(in, out, in->rank, in->shape, is, os, 0, lo * os[dim], stream);
+}
+
+int glenside_pair(const gs_ap* a, const gs_ap* b, gs_ap* out, void* stream) {
+  int st = check_ap(a, true);
+  if (st) return st;
+  st = check_ap(b, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if ((out->data && out->data == a->data) || (out->data && out->data == b->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (a->rank != b->rank || a->n_access != b->n_access) return GS_ERR_RANK;
+  if (!same_shape(a, b)) return GS_ERR_SHAPE;
+  if (a->dtype != b->dtype) return GS_ERR_DTYPE;
+  if (a->rank + 1 > GS_MAX_RANK) return GS_ERR_RANK;
+  int64_t shape[GS_MAX_RANK];
+  for (int d = 0; d < a->n_access; ++d) shape[d] = a->shape[d];
+  shape[a->n_access] = 2;
+  for (int d = a->n_access; d < a->rank; ++d) shape[d + 1] = a->shape[d];
+  st = check_result(out, a->dtype, a->rank + 1, a->n_access, shape);
+  if (st) return st;
+  // ((A..),(C..)) seen as [A][C]; the output as [A][2][C].
+  const int64_t A = access_numel(a), C = compute_numel(a);
+  const int64_t dims[2] = {A, C}, is[2] = {C, 1}, os[2] = {2 * C, 1};
+  st = run_move(a, out, 2, dims, is, os, 0, 0, stream);
+  if (st) return st;
+  return run_move(b, out, 2, dims, is, os, 0, C, stream);
+}
+
 }  // extern "C"

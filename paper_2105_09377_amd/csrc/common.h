@@ -198,6 +198,17 @@ struct WindowsArgs {      // generic N-d windows over the compute dims
 };
 hipError_t launch_windows(const WindowsArgs& a, hipStream_t s);
 
+struct MoveArgs {         // out[out_off + sum i_d os[d]] = in[in_off + sum i_d is[d]], 0 <= i_d < dims[d]
+  const void* in;
+  void* out;
+  int esz;                // element size in bytes: 1, 2 or 4
+  int rank;               // at most 8
+  int64_t dims[8], is[8], os[8];   // extents and element strides, in the output's dimension order
+  int64_t in_off, out_off;         // element offsets
+};
+hipError_t launch_move(const MoveArgs& a, hipStream_t s);
+hipError_t launch_fill(void* out, int esz, int64_t n, uint32_t bits, hipStream_t s);
+
 struct GemmArgs {         // C[i][j] = sum_k X[i][k] * Y[j][k]
   const void* x;          // I x K, row stride ldx elements
   const void* y;          // J x K, row stride ldy elements

@@ -127,6 +127,40 @@ def test_reduce_and_pair_validation():
     assert pr(ap((4, 5), 1, gs.GS_F32), ap((4, 5), 1, gs.GS_F32), y) == gs.GS_ERR_RANK   # compute dims would be folded
 
 
+def test_transformer_validation():
+    """Table 1 shape rules of transpose / slice / concat / pair (and the pad extension)."""
+    L = gs.lib()
+    x = ap((4, 5, 6), 1)
+    other = 0x20000
+    tr = lambda a, perm, out: L.glenside_transpose(ctypes.byref(a), i64(*perm), ctypes.byref(out), None)
+    assert tr(x, (0, 0, 1), ap((4, 4, 5), 1, data=other)) == gs.GS_ERR_SHAPE          # not a permutation
+    assert tr(x, (2, 0, 1), ap((6, 4, 6), 1, data=other)) == gs.GS_ERR_SHAPE          # result is (6, 4, 5)
+    assert tr(x, (2, 0, 1), ap((6, 4, 5), 2, data=other)) == gs.GS_ERR_RANK           # the split stays at 1
+    assert tr(x, (2, 0, 1), ap((6, 4, 5), 1, gs.GS_F32, data=other)) == gs.GS_ERR_DTYPE
+    assert tr(x, (2, 0, 1), ap((6, 4, 5), 1)) == gs.GS_ERR_UNSUPPORTED                 # in place
+    assert L.glenside_transpose(ctypes.byref(x), None, ctypes.byref(ap((6, 4, 5), 1, data=other)), None) == gs.GS_ERR_NULL
+    sl = lambda a, d, lo, hi, out: L.glenside_slice(ctypes.byref(a), d, lo, hi, ctypes.byref(out), None)
+    assert sl(x, 3, 0, 1, ap((4, 5, 6), 1, data=other)) == gs.GS_ERR_RANK
+    assert sl(x, 1, 2, 6, ap((4, 4, 6), 1, data=other)) == gs.GS_ERR_SHAPE            # hi past the extent
+    assert sl(x, 1, 3, 2, ap((4, 0, 6), 1, data=other)) == gs.GS_ERR_SHAPE            # lo > hi
+    assert sl(x, 1, 1, 3, ap((4, 3, 6), 1, data=other)) == gs.GS_ERR_SHAPE            # result is (4, 2, 6)
+    cc = lambda a, b, d, out: L.glenside_concat(ctypes.byref(a), ctypes.byref(b), d, ctypes.byref(out), None)
+    assert cc(x, ap((4, 5, 7), 1), 1, ap((4, 10, 6), 1, data=other)) == gs.GS_ERR_SHAPE   # other dims differ
+    assert cc(x, ap((4, 5, 6), 2), 1, ap((4, 10, 6), 1, data=other)) == gs.GS_ERR_RANK    # access splits differ
+    assert cc(x, ap((4, 2, 6), 1), 1, ap((4, 8, 6), 1, data=other)) == gs.GS_ERR_SHAPE    # result is (4, 7, 6)
+    assert cc(x, ap((4, 2, 6), 1, gs.GS_F32), 1, ap((4, 7, 6), 1, data=other)) == gs.GS_ERR_DTYPE
+    pd = lambda a, d, lo, hi, mode, out: L.glenside_pad(ctypes.byref(a), d, lo, hi, mode, ctypes.byref(out), None)
+    assert pd(x, 2, -1, 0, gs.GS_PAD_ZERO, ap((4, 5, 5), 1, data=other)) == gs.GS_ERR_SHAPE
+    assert pd(x, 2, 1, 2, 7, ap((4, 5, 9), 1, data=other)) == gs.GS_ERR_UNSUPPORTED
+    assert pd(x, 2, 1, 2, gs.GS_PAD_ZERO, ap((4, 5, 8), 1, data=other)) == gs.GS_ERR_SHAPE
+    pr = lambda a, b, out: L.glenside_pair(ctypes.byref(a), ctypes.byref(b), ctypes.byref(out), None)
+    assert pr(x, ap((4, 5, 7), 1), ap((4, 2, 5, 6), 1, data=other)) == gs.GS_ERR_SHAPE
+    assert pr(x, x, ap((4, 5, 2, 6), 1, data=other)) == gs.GS_ERR_SHAPE               # the 2 leads the compute dims
+    assert pr(x, x, ap((4, 2, 5, 6), 2, data=other)) == gs.GS_ERR_RANK
+    full = ap((1,) * 8, 4)
+    assert pr(full, full, ap((1,) * 8, 4, data=other)) == gs.GS_ERR_RANK              # rank 9 does not exist
+
+
 def test_windows_reduce_validation():
     L = gs.lib()
     call = lambda a, win, st, out, op=gs.GS_MAX: L.glenside_windows_reduce(

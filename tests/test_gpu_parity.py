@@ -382,3 +382,102 @@ def test_pair_reduce(dtype, op):
     pr = ap.pair(ap.access(ap.tensor(to_oracle(a)), 4), ap.access(ap.tensor(to_oracle(b)), 4))
     want = ap.compute(ap.relu, ap.compute(oper, pr)).materialize()
     assert_parity(got, want, float_tol=1e-2 if dtype == "bf16" else 1e-6)
+
+
+# ---------------------------------------------------------------------------------------------
+# transformers that move data: transpose, slice, concat, pair, pad
+# ---------------------------------------------------------------------------------------------
+
+def assert_same_values(got, node, what):
+    """A transformer only moves elements: the stored values must be the oracle's, exactly."""
+    want = node.materialize()
+    assert tuple(got.shape) == tuple(want.shape), what
+    np.testing.assert_array_equal(to_oracle(got), want, err_msg=what)
+
+
+TRANSPOSE_CASES = [
+    # dtype, shape, n_access, perm
+    ("bf16", (3, 20, 20, 24), 1, (0, 3, 1, 2)),      # the (N,H',W',O) -> (N,O,H',W') tail of Fig. 5
+    ("f32", (70, 130), 1, (1, 0)),                   # ((N),(O)) -> ((O),(N)), ragged 64 x 64 tiles
+    ("i8", (5, 67, 33), 2, (0, 2, 1)),
+    ("i32", (4, 3, 5, 6), 2, (3, 1, 0, 2)),          # no dimension keeps its place
+    ("bf16", (6, 7, 64), 1, (1, 0, 2)),              # the contiguous dimension stays: rows are copied
+    ("bf16", (2, 3, 4, 5, 6), 3, (4, 3, 2, 1, 0)),
+    ("f32", (9,), 1, (0,)),
+]
+
+
+@pytest.mark.parametrize("case", TRANSPOSE_CASES)
+def test_transpose(case):
+    dtype, shape, na, perm = case
+    x = gen(dtype, shape, 2100 + len(shape) + shape[0])
+    got = gs.transpose(x.to(DEV), na, perm)
+    assert_same_values(got, ap.transpose(ap.access(ap.tensor(to_oracle(x)), na), perm), str(case))
+
+
+SLICE_CASES = [
+    ("bf16", (4, 64, 40), 1, 1, 8, 56), ("i8", (37, 19), 1, 1, 3, 17), ("f32", (10, 6, 8), 2, 0, 2, 9),
+    ("i32", (5, 12), 1, 1, 4, 4), ("bf16", (3, 5, 7, 16), 2, 2, 1, 6),
+]
+
+
+@pytest.mark.parametrize("case", SLICE_CASES)
+def test_slice(case):
+    dtype, shape, na, dim, lo, hi = case
+    x = gen(dtype, shape, 2200 + shape[0])
+    got = gs.slice_(x.to(DEV), na, dim, lo, hi)
+    assert_same_values(got, ap.slice_(ap.access(ap.tensor(to_oracle(x)), na), dim, lo, hi), str(case))
+
+
+CONCAT_CASES = [
+    ("bf16", (4, 24, 32), (4, 40, 32), 1, 1), ("i8", (3, 5), (3, 9), 1, 1), ("f32", (2, 6, 8), (5, 6, 8), 1, 0),
+    ("i32", (4, 3, 0), (4, 3, 5), 2, 2), ("bf16", (2, 3, 4, 8), (2, 3, 4, 24), 2, 3),
+]
+
+
+@pytest.mark.parametrize("case", CONCAT_CASES)
+def test_concat(case):
+    dtype, sa, sb, na, dim = case
+    a, b = gen(dtype, sa, 2300 + sa[0]), gen(dtype, sb, 2310 + sb[0])
+    got = gs.concat(a.to(DEV), b.to(DEV), na, dim)
+    node = ap.concat(ap.access(ap.tensor(to_oracle(a)), na), ap.access(ap.tensor(to_oracle(b)), na), dim)
+    assert_same_values(got, node, str(case))
+
+
+@pytest.mark.parametrize("case", [("bf16", (6, 5, 16), 1), ("i8", (7, 3), 1), ("f32", (4, 9, 2), 2),
+                                  ("i32", (5, 8), 2), ("bf16", (33, 64), 0)])
+def test_pair(case):
+    dtype, shape, na = case
+    a, b = gen(dtype, shape, 2400 + shape[0]), gen(dtype, shape, 2410 + shape[0])
+    got = gs.pair(a.to(DEV), b.to(DEV), na)
+    node = ap.pair(ap.access(ap.tensor(to_oracle(a)), na), ap.access(ap.tensor(to_oracle(b)), na))
+    assert_same_values(got, node, str(case))
+
+
+@pytest.mark.parametrize("case", [("bf16", (3, 8, 16), 1, 2, 8, 8, gs.GS_PAD_ZERO), ("i8", (5, 7), 1, 1, 2, 3, gs.GS_PAD_LOWEST),
+                                  ("f32", (4, 6, 5), 2, 1, 1, 0, gs.GS_PAD_LOWEST), ("i32", (2, 9), 1, 0, 0, 0, gs.GS_PAD_ZERO)])
+def test_pad(case):
+    dtype, shape, na, dim, lo, hi, mode = case
+    x = gen(dtype, shape, 2500 + shape[0])
+    got = gs.pad(x.to(DEV), na, dim, lo, hi, mode)
+    fill = LOWEST[dtype] if mode == gs.GS_PAD_LOWEST else 0
+    assert_same_values(got, ap.pad(ap.access(ap.tensor(to_oracle(x)), na), dim, lo, hi, fill), str(case))
+
+
+def test_blocked_matmul_from_slices_and_concat():
+    """Fig. 7 on the GPU: a matmul split in two along N and K with slice, cartProd/dotProd on the
+    blocks, pair + reduceSum over the K halves and concat along N equals the unblocked product
+    (exactly, for integers)."""
+    a = gen("i8", (48, 128), 2601)
+    b = gen("i8", (80, 128), 2602)
+    A, B = a.to(DEV), b.to(DEV)
+    whole = gs.cartesian_dot(A, B)
+    cols = []
+    for n0, n1 in ((0, 32), (32, 80)):
+        bn = gs.slice_(B, 1, 0, n0, n1)
+        halves = [gs.cartesian_dot(gs.slice_(A, 1, 1, k0, k0 + 64), gs.slice_(bn, 1, 1, k0, k0 + 64)) for k0 in (0, 64)]
+        cols.append(gs.pair_reduce(halves[0], halves[1], gs.GS_SUM))
+    blocked = gs.concat(cols[0], cols[1], 2, 1)
+    assert torch.equal(blocked, whole)
+    prog = pg.cartesian_dot(ap.access(ap.tensor(to_oracle(a)), 1), ap.access(ap.tensor(to_oracle(b)), 1))
+    assert_parity(blocked, prog.materialize(), what="blocked matmul")
