@@ -40,19 +40,21 @@ KERNEL_SOURCES = {
     "conv": ("conv4_kernel.h", "conv_kernels.h", "conv3_inst.hip", "conv.hip", "common.h"),
     "windows": ("windows.hip", "common.h"),
     "reduce": ("reduce.hip", "common.h"),
+    "move": ("move.hip", "common.h"),
     "gemm": ("gemm.hip", "common.h"),
 }
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (27.06e6 + 25.70e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
-    "conv3x3": (14.21e6 + 12.85e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),
-    "conv3x3_b64": (27.06e6 + 25.70e6, "conv", "fef2717b2f2d34f0c60228d3a5dabbdb0029894ffd087d9ac968371adcc0a193"),
-    "im2col_gather": (12.97e6 + 115.65e6, "windows", "6ab63993fd0789bc760165f2af88d90a47cd8eb668fe1f07ef0387bf9e5ff547"),
-    "maxpool": (102.99e6 + 25.69e6, "reduce", "82db2f73ebcc5d12f430d500a7f90c3a2157c90f69bbeb327ad69fbd36c16757"),
-    "reduce": (268.44e6 + 0.52e6, "reduce", "82db2f73ebcc5d12f430d500a7f90c3a2157c90f69bbeb327ad69fbd36c16757"),
-    "dense": (1634.29e6 + 274.42e6, "gemm", "6215efc06f467af8b959fc0f0ad129d35fc7796084fd7153b0ba22d09f46310a"),
-    "mlp_scaled": (29.33e6 + 16.78e6, "gemm", "6215efc06f467af8b959fc0f0ad129d35fc7796084fd7153b0ba22d09f46310a"),
+    "resnet18": (27.06e6 + 25.70e6, "conv", "4ebf63857bc68278605d03281a72280ddce866b7d4199408f60a0a8f11eff7e3"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
+    "conv3x3": (14.21e6 + 12.85e6, "conv", "4ebf63857bc68278605d03281a72280ddce866b7d4199408f60a0a8f11eff7e3"),
+    "conv3x3_b64": (27.06e6 + 25.70e6, "conv", "4ebf63857bc68278605d03281a72280ddce866b7d4199408f60a0a8f11eff7e3"),
+    "im2col_gather": (12.97e6 + 115.65e6, "windows", "8f213e3d6e591679d90f6e8ac8b07596ca76345f9b6d3594b7300899d3b80672"),
+    "maxpool": (102.99e6 + 25.69e6, "reduce", "9eb204f97458193b5ff9a1e28624d7ce9aa9d701c334204564151583e275147e"),
+    "reduce": (268.44e6 + 0.52e6, "reduce", "9eb204f97458193b5ff9a1e28624d7ce9aa9d701c334204564151583e275147e"),
+    "transpose": (25.76e6 + 25.70e6, "move", "51ea9bb799d81af55674aeeb70557e247c1f0d9205b92f83666c6b67f5baa81f"),
+    "dense": (1635.93e6 + 274.91e6, "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),
+    "mlp_scaled": (29.33e6 + 16.78e6, "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),
 }
 
 
@@ -279,6 +281,35 @@ class MaxPool(_Simple):
                 "sample": f"brute-force C loops (fp64, OpenMP) on the whole tensor, {dt:.2f} s"}
 
 
+class Transpose(_Simple):
+    """transpose (0 3 1 2): the (N,H',W',O) -> (N,O,H',W') tail of the im2col convolution listing,
+    at the size of the stack's stage-1 result (batch 64), bf16."""
+
+    name = "transpose (0 3 1 2) of ((64),(56,56,64)) bf16 -> (64,64,56,56)"
+    dominant = "move_transpose_kernel"
+
+    def __init__(self, dev):
+        from paper_2105_09377_amd import binding as gs, synth
+        self.gs = gs
+        self.x = synth.normal_bf16((64, 56, 56, 64), 1.0, 7301)
+        self.work = 2 * self.x.numel() * 2
+        self.nsets = self._sets(self.work, 6)
+        self.xs = [self.x.to(dev).clone() for _ in range(self.nsets)]
+        self.outs = [torch.empty((64, 64, 56, 56), dtype=torch.bfloat16, device=dev) for _ in range(self.nsets)]
+
+    def step(self, i):
+        self.gs.transpose(self.xs[i], 1, (0, 3, 1, 2), out=self.outs[i])
+
+    def cpu_baseline(self):
+        from oracle import access_pattern as ap
+        x = _bf16_to_f64(self.x[:8])
+        t0 = time.perf_counter()
+        ap.transpose(ap.access(ap.tensor(x), 1), (0, 3, 1, 2)).materialize()
+        dt = time.perf_counter() - t0
+        return {"value": self.work / 8 / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                "sample": f"the access-pattern interpreter (numpy gather, fp64) on 8 of the 64 images, {dt:.2f} s"}
+
+
 class RowReduce(_Simple):
     """compute reduceSum over ((65536),(1024)) fp32."""
 
@@ -395,7 +426,7 @@ class MlpScaled(Mlp):
 
 
 WORKLOADS = {"conv3x3": Conv3x3, "conv3x3_b64": Conv3x3Batch64, "resnet18": ResNet18, "im2col_gather": Im2colGather, "maxpool": MaxPool,
-             "reduce": RowReduce, "dense": DenseBig, "mlp": Mlp, "mlp_scaled": MlpScaled}
+             "reduce": RowReduce, "transpose": Transpose, "dense": DenseBig, "mlp": Mlp, "mlp_scaled": MlpScaled}
 
 
 def main():

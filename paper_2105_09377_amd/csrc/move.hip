@@ -9,7 +9,8 @@
 // work is pure HBM traffic: |in| + |out| bytes.  Three kernels:
 //   * move_rows_kernel      the last dimension is contiguous on both sides: rows of 16-byte vectors;
 //   * move_transpose_kernel the input's contiguous dimension is not the output's: 64 x 64 tiles
-//                           through LDS, so that both the reads and the writes are coalesced;
+//                           through LDS, so that both the reads and the writes are coalesced
+//                           (8 bytes per lane on both sides when everything is 8-byte aligned);
 //   * move_generic_kernel   anything else, one element per thread.
 #include "common.h"
 
@@ -46,19 +47,21 @@ __global__ void __launch_bounds__(256) move_generic_kernel(MoveK k) {
 }
 
 // Last dimension contiguous on both sides and a whole number of 16-byte vectors, every other
-// stride and both bases multiples of 16 bytes.  G threads share a row (G a power of two).
+// stride and both bases multiples of 16 bytes.  A row is cut into segments of `seg` vectors; G
+// threads (a power of two) share one (row, segment) unit.
 struct RowsK {
   MoveK m;                        // m.dims[rank-1] is the row length in VECTORS; strides in vectors
-  int64_t rows;
+  int64_t rows, nseg, seg;
   int G;
 };
 __global__ void __launch_bounds__(256) move_rows_kernel(RowsK k) {
   const i32x4* in = reinterpret_cast<const i32x4*>(k.m.in);
   i32x4* out = reinterpret_cast<i32x4*>(k.m.out);
   const int G = k.G, lane = threadIdx.x & (G - 1);
-  const int64_t rows_per_step = int64_t(gridDim.x) * (256 / G);
+  const int64_t units_per_step = int64_t(gridDim.x) * (256 / G), units = k.rows * k.nseg;
   const int64_t nv = k.m.dims[k.m.rank - 1];
-  for (int64_t row = int64_t(blockIdx.x) * (256 / G) + threadIdx.x / G; row < k.rows; row += rows_per_step) {
+  for (int64_t unit = int64_t(blockIdx.x) * (256 / G) + threadIdx.x / G; unit < units; unit += units_per_step) {
+    const int64_t row = unit / k.nseg, sg = unit - row * k.nseg;
     int64_t r = row, io = 0, oo = 0;
     for (int d = k.m.rank - 2; d >= 0; --d) {
       const int64_t q = r / k.m.dims[d], i = r - q * k.m.dims[d];
@@ -66,7 +69,8 @@ __global__ void __launch_bounds__(256) move_rows_kernel(RowsK k) {
       oo += i * k.m.os[d];
       r = q;
     }
-    for (int64_t v = lane; v < nv; v += G)
+    const int64_t v0 = sg * k.seg, v1 = v0 + k.seg < nv ? v0 + k.seg : nv;
+    for (int64_t v = v0 + lane; v < v1; v += G)
       __builtin_nontemporal_store(__builtin_nontemporal_load(in + io + v), out + oo + v);
   }
 }
@@ -112,6 +116,59 @@ __global__ void __launch_bounds__(256) move_transpose_kernel(TransK k) {
   for (int j = ty; j < 64; j += 4) {                          // A index a0 + j, threads along B
     const int64_t a = a0 + j, b = b0 + tx;
     if (a < k.EA && b < k.EB) out[oo + a * k.sA_out + b] = tile[tx][j];
+  }
+}
+
+// The same with 8 bytes per lane on both sides (extents, strides and bases whole numbers of
+// 8-byte vectors): a thread reads NV = 8 / sizeof(T) elements along A, and writes NV along B that
+// it collects from NV rows of the LDS tile.
+template <typename T>
+__global__ void __launch_bounds__(256) move_transpose_vec_kernel(TransK k) {
+  constexpr int ESZ = int(sizeof(T)), NV = 8 / ESZ;
+  constexpr int TPR = 64 / NV, RPP = 256 / TPR, NP = 64 / RPP;   // threads per tile row, rows per pass, passes
+  constexpr int PITCH = 64 + 4 / ESZ;                            // tile row: a whole number of dwords, odd in dwords
+  __shared__ __attribute__((aligned(8))) T tile[64 * PITCH];
+  const T* in = reinterpret_cast<const T*>(k.in);
+  T* out = reinterpret_cast<T*>(k.out);
+  int64_t t = blockIdx.x;
+  const int64_t ta = t % k.tilesA;
+  t /= k.tilesA;
+  const int64_t tb = t % k.tilesB;
+  t /= k.tilesB;
+  int64_t io = 0, oo = 0;
+  for (int d = k.nb - 1; d >= 0; --d) {
+    const int64_t q = t / k.bdims[d], i = t - q * k.bdims[d];
+    io += i * k.bis[d];
+    oo += i * k.bos[d];
+    t = q;
+  }
+  const int64_t a0 = ta * 64, b0 = tb * 64;
+  const int c = threadIdx.x % TPR, r = threadIdx.x / TPR;
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const int j = p * RPP + r;
+    const int64_t a = a0 + c * NV, b = b0 + j;
+    if (a < k.EA && b < k.EB) {
+      const i32x2 v = __builtin_nontemporal_load(reinterpret_cast<const i32x2*>(in + io + b * k.sB_in + a));
+      uint32_t* d = reinterpret_cast<uint32_t*>(&tile[j * PITCH + c * NV]);
+      d[0] = uint32_t(v.x);
+      d[1] = uint32_t(v.y);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const int ja = p * RPP + r;
+    const int64_t a = a0 + ja, b = b0 + c * NV;
+    if (a < k.EA && b < k.EB) {
+      union {
+        T e[NV];
+        i32x2 v;
+      } u;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) u.e[i] = tile[(c * NV + i) * PITCH + ja];
+      __builtin_nontemporal_store(u.v, reinterpret_cast<i32x2*>(out + oo + a * k.sA_out + b));
+    }
   }
 }
 
@@ -184,10 +241,13 @@ hipError_t launch_move(const MoveArgs& a, hipStream_t s) {
         r.m.os[d] = k.os[d] / epv;
       }
       r.rows = k.total / k.dims[last];
+      r.seg = 1024;                                   // 16 KB per unit
+      r.nseg = ceil_div(r.m.dims[last], r.seg);
+      const int64_t per_unit = r.m.dims[last] < r.seg ? r.m.dims[last] : r.seg;
       int G = 256;
-      while (G > 1 && G / 2 >= r.m.dims[last]) G /= 2;
+      while (G > 1 && G / 2 >= per_unit) G /= 2;
       r.G = G;
-      const int64_t want = ceil_div(r.rows, 256 / G);
+      const int64_t want = ceil_div(r.rows * r.nseg, 256 / G);
       hipLaunchKernelGGL(move_rows_kernel, dim3(unsigned(want < 16384 ? want : 16384)), dim3(256), 0, s, r);
       return hipGetLastError();
     }
@@ -220,6 +280,16 @@ hipError_t launch_move(const MoveArgs& a, hipStream_t s) {
       t.tilesA = ceil_div(t.EA, 64);
       t.tilesB = ceil_div(t.EB, 64);
       const int64_t blocks = t.tilesA * t.tilesB * batch;
+      const int64_t nv = 8 / esz;
+      bool vec8 = t.EA % nv == 0 && t.EB % nv == 0 && t.sA_out % nv == 0 && t.sB_in % nv == 0 &&
+                  reinterpret_cast<uintptr_t>(t.in) % 8 == 0 && reinterpret_cast<uintptr_t>(t.out) % 8 == 0;
+      for (int d = 0; d < t.nb && vec8; ++d) vec8 = t.bis[d] % nv == 0 && t.bos[d] % nv == 0;
+      if (blocks <= 0x7fffffff && vec8) {
+        if (esz == 1) hipLaunchKernelGGL((move_transpose_vec_kernel<uint8_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
+        else if (esz == 2) hipLaunchKernelGGL((move_transpose_vec_kernel<uint16_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
+        else hipLaunchKernelGGL((move_transpose_vec_kernel<uint32_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
+        return hipGetLastError();
+      }
       if (blocks <= 0x7fffffff) {
         if (esz == 1) hipLaunchKernelGGL((move_transpose_kernel<uint8_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
         else if (esz == 2) hipLaunchKernelGGL((move_transpose_kernel<uint16_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);

@@ -404,6 +404,8 @@ TRANSPOSE_CASES = [
     ("bf16", (6, 7, 64), 1, (1, 0, 2)),              # the contiguous dimension stays: rows are copied
     ("bf16", (2, 3, 4, 5, 6), 3, (4, 3, 2, 1, 0)),
     ("f32", (9,), 1, (0,)),
+    ("i8", (2, 64, 136), 1, (0, 2, 1)),              # 8 elements per lane
+    ("bf16", (3, 7, 9), 1, (0, 2, 1)),               # odd extents: one element per lane
 ]
 
 
