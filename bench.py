@@ -370,6 +370,42 @@ class DenseBig(_Simple):
                 "kind": "oracle", "sample": f"brute-force C loops (fp64, OpenMP) on a 256 x 512 block of the result, {dt:.2f} s"}
 
 
+class DenseBlocked(_Simple):
+    """The blocked form of the product (slice / dotProd / pair + reduceSum / concat, one launch per
+    block and K slice) on 2048 x 2048 x 2048 bf16 with cubic blocks of TILE: the tile-shape sweep
+    of the paper's systolic-array sizes.  TILE = 2048 is the unblocked product."""
+
+    TILE = 512
+    dominant = "gemm_nt_* (one launch per block and K slice)"
+    bound, unit, peak = "mfma", "TFLOP/s", PEAK_BF16_TFLOPS
+    name = property(lambda self: f"cartesian_dot_blocked 2048^3 bf16 -> f32, blocks of {self.TILE}^3 "
+                                 f"({(2048 // self.TILE) ** 3} launches per step)")
+
+    def __init__(self, dev):
+        from paper_2105_09377_amd import binding as gs, synth
+        self.gs = gs
+        self.a = synth.normal_bf16((2048, 2048), 1.0, 7401)
+        self.b = synth.normal_bf16((2048, 2048), 2048 ** -0.5, 7402)
+        self.work = 2.0 * 2048 ** 3
+        self.nsets = 4
+        self.as_ = [self.a.to(dev).clone() for _ in range(self.nsets)]
+        self.bs = [self.b.to(dev).clone() for _ in range(self.nsets)]
+        self.outs = [torch.empty((2048, 2048), dtype=torch.float32, device=dev) for _ in range(self.nsets)]
+
+    def step(self, i):
+        t = self.TILE
+        self.gs.cartesian_dot_blocked(self.as_[i], self.bs[i], t, t, t, out=self.outs[i])
+
+    def cpu_baseline(self):
+        from oracle import brute
+        a, b = _bf16_to_f64(self.a[:512]), _bf16_to_f64(self.b[:512])
+        t0 = time.perf_counter()
+        brute.matmul(a, b.T)
+        dt = time.perf_counter() - t0
+        return {"value": 2.0 * 512 * 512 * 2048 / dt / 1e12, "unit": "TFLOP/s", "cores": brute.num_threads(),
+                "kind": "oracle", "sample": f"brute-force C loops (fp64, OpenMP) on a 512 x 512 block of the result, {dt:.2f} s"}
+
+
 class Mlp(_Simple):
     """The dense MLP workload (batch 256, 784-512-512-10, ReLU) as three cartesian_dot calls."""
 
@@ -426,7 +462,7 @@ class MlpScaled(Mlp):
 
 
 WORKLOADS = {"conv3x3": Conv3x3, "conv3x3_b64": Conv3x3Batch64, "resnet18": ResNet18, "im2col_gather": Im2colGather, "maxpool": MaxPool,
-             "reduce": RowReduce, "transpose": Transpose, "dense": DenseBig, "mlp": Mlp, "mlp_scaled": MlpScaled}
+             "reduce": RowReduce, "transpose": Transpose, "dense": DenseBig, "dense_blocked": DenseBlocked, "mlp": Mlp, "mlp_scaled": MlpScaled}
 
 
 def main():
@@ -435,6 +471,8 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="resnet18", choices=sorted(WORKLOADS))
+    ap.add_argument("--tile", type=int, default=None,
+                    help="dense_blocked only: edge of the cubic blocks (a divisor of 2048, at least 128; default 512)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB -> 256 MiB elementwise copy 10 times and exit (reference "
@@ -456,6 +494,10 @@ def main():
         print(json.dumps({"calibrate_copy": {"launches": 10, "read_bytes": src.numel() * 4,
                                              "write_bytes": dst.numel() * 4}}))
         return
+    if args.tile is not None:
+        if args.workload != "dense_blocked" or args.tile < 128 or 2048 % args.tile:
+            sys.exit("--tile needs --workload dense_blocked and a divisor of 2048 that is at least 128")
+        DenseBlocked.TILE = args.tile
     wl = WORKLOADS[args.workload](dev)
     stream = torch.cuda.Stream(device=dev)
 

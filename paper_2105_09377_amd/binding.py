@@ -33,7 +33,7 @@ EXPORTS = (
     "glenside_conv2d_direct_workspace", "glenside_conv2d_im2col_workspace", "glenside_reduce",
     "glenside_windows_reduce", "glenside_pair_reduce", "glenside_conv2d_pack_weights",
     "glenside_conv2d_direct_packed", "glenside_transpose", "glenside_slice", "glenside_concat",
-    "glenside_pad", "glenside_pair",
+    "glenside_pad", "glenside_pair", "glenside_cartesian_dot_blocked",
 )
 
 
@@ -82,6 +82,7 @@ def lib() -> ctypes.CDLL:
         L.glenside_concat.argtypes = [ap_p, ap_p, ctypes.c_int, ap_p, vp]
         L.glenside_pad.argtypes = [ap_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ap_p, vp]
         L.glenside_pair.argtypes = [ap_p, ap_p, ap_p, vp]
+        L.glenside_cartesian_dot_blocked.argtypes = [ap_p, ap_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ap_p, vp]
         _lib = L
     return _lib
 
@@ -339,4 +340,16 @@ def pair(a: torch.Tensor, b: torch.Tensor, n_access: int, out: Optional[torch.Te
         out = torch.empty(shape, dtype=a.dtype, device=a.device)
     _check(lib().glenside_pair(ctypes.byref(make_ap(a, n_access)), ctypes.byref(make_ap(b, n_access)),
                                ctypes.byref(make_ap(out, n_access)), _stream(a)), "pair")
+    return out
+
+
+def cartesian_dot_blocked(a0: torch.Tensor, a1: torch.Tensor, tile_m: int, tile_n: int, tile_k: int,
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The blocked form of compute dotProd (cartProd a0 a1) for matrices ((M),(K)) x ((N),(K))."""
+    if out is None:
+        out_dtype = torch.int32 if a0.dtype == torch.int8 else torch.float32
+        out = torch.empty((a0.shape[0], a1.shape[0]), dtype=out_dtype, device=a0.device)
+    _check(lib().glenside_cartesian_dot_blocked(ctypes.byref(make_ap(a0, 1)), ctypes.byref(make_ap(a1, 1)),
+                                                tile_m, tile_n, tile_k, ctypes.byref(make_ap(out, 2)),
+                                                _stream(a0)), "cartesian_dot_blocked")
     return out

@@ -254,6 +254,61 @@ int glenside_cartesian_dot(const gs_ap* a0, const gs_ap* a1, gs_ap* out, int act
   return launch_status(launch_gemm(g, static_cast<hipStream_t>(stream)));
 }
 
+int glenside_cartesian_dot_blocked(const gs_ap* a0, const gs_ap* a1, int64_t tile_m, int64_t tile_n,
+                                   int64_t tile_k, gs_ap* out, void* stream) {
+  int st = check_ap(a0, true);
+  if (st) return st;
+  st = check_ap(a1, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  // The blocked form is stated for matrices: a0 ((M),(K)), a1 ((N),(K)), out ((M,N),()).
+  if (a0->rank != 2 || a0->n_access != 1 || a1->rank != 2 || a1->n_access != 1) return GS_ERR_RANK;
+  if (out->rank != 2 || out->n_access != 2) return GS_ERR_RANK;
+  if (a0->shape[1] != a1->shape[1]) return GS_ERR_SHAPE;
+  if (out->shape[0] != a0->shape[0] || out->shape[1] != a1->shape[0]) return GS_ERR_SHAPE;
+  if (tile_m < 1 || tile_n < 1 || tile_k < 1) return GS_ERR_SHAPE;
+  if (a0->dtype != a1->dtype) return GS_ERR_DTYPE;
+  // Partial sums of the K blocks are folded in the result, which therefore has the accumulator's type.
+  if (a0->dtype == GS_I8) {
+    if (out->dtype != GS_I32) return GS_ERR_DTYPE;
+  } else if (a0->dtype == GS_BF16) {
+    if (out->dtype != GS_F32) return GS_ERR_DTYPE;
+  } else {
+    return GS_ERR_DTYPE;
+  }
+  const int64_t M = a0->shape[0], N = a1->shape[0], K = a0->shape[1];
+  if (M == 0 || N == 0) return GS_OK;
+  const int64_t launches = ceil_div(M, tile_m) * ceil_div(N, tile_n) * (K > 0 ? ceil_div(K, tile_k) : 1);
+  if (launches > 65536) return GS_ERR_UNSUPPORTED;
+  const size_t esz = dtype_size(a0->dtype);
+  for (int64_t m0 = 0; m0 < M; m0 += tile_m)
+    for (int64_t n0 = 0; n0 < N; n0 += tile_n) {
+      // dotProd over (slice a0 [m0,m1) x [k0,k1)) x (slice a1 [n0,n1) x [k0,k1)); the K blocks are
+      // folded left to right as reduceSum (pair acc part), i.e. added to the block already stored.
+      int64_t k0 = 0;
+      do {
+        GemmArgs g{};
+        memset(&g, 0, sizeof(g));
+        g.x = static_cast<const uint8_t*>(a0->data) + (m0 * K + k0) * esz;
+        g.y = static_cast<const uint8_t*>(a1->data) + (n0 * K + k0) * esz;
+        g.out = static_cast<uint8_t*>(out->data) + (m0 * N + n0) * 4;
+        g.residual = k0 > 0 ? g.out : nullptr;
+        g.in_dtype = a0->dtype;
+        g.out_dtype = out->dtype;
+        g.I = M - m0 < tile_m ? M - m0 : tile_m;
+        g.J = N - n0 < tile_n ? N - n0 : tile_n;
+        g.K = K - k0 < tile_k ? K - k0 : tile_k;
+        g.ldx = g.ldy = K;
+        g.jp = N;                         // rows of the block are N apart in the result
+        st = launch_status(launch_gemm(g, static_cast<hipStream_t>(stream)));
+        if (st) return st;
+        k0 += tile_k;
+      } while (k0 < K);
+    }
+  return GS_OK;
+}
+
 size_t glenside_conv2d_direct_workspace(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
                                         const int64_t pad[2]) {
   ConvShape cs;

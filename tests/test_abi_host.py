@@ -161,6 +161,21 @@ def test_transformer_validation():
     assert pr(full, full, ap((1,) * 8, 4, data=other)) == gs.GS_ERR_RANK              # rank 9 does not exist
 
 
+def test_blocked_dot_validation():
+    L = gs.lib()
+    call = lambda a0, a1, tm, tn, tk, out: L.glenside_cartesian_dot_blocked(
+        ctypes.byref(a0), ctypes.byref(a1), tm, tn, tk, ctypes.byref(out), None)
+    a0, a1 = ap((64, 128), 1), ap((32, 128), 1)
+    out = ap((64, 32), 2, gs.GS_F32, data=0x20000)
+    assert call(a0, a1, 0, 16, 16, out) == gs.GS_ERR_SHAPE                         # tile sizes start at 1
+    assert call(a0, ap((32, 64), 1), 16, 16, 16, out) == gs.GS_ERR_SHAPE           # compute shapes differ
+    assert call(a0, a1, 16, 16, 16, ap((64, 32), 2, gs.GS_BF16, data=0x20000)) == gs.GS_ERR_DTYPE   # folds need 32 bits
+    assert call(a0, a1, 16, 16, 16, ap((64, 33), 2, gs.GS_F32, data=0x20000)) == gs.GS_ERR_SHAPE
+    assert call(ap((4, 16, 128), 2), a1, 16, 16, 16, out) == gs.GS_ERR_RANK        # stated for matrices
+    big0, big1 = ap((4096, 4096), 1), ap((4096, 4096), 1)
+    assert call(big0, big1, 16, 16, 16, ap((4096, 4096), 2, gs.GS_F32, data=0x20000)) == gs.GS_ERR_UNSUPPORTED
+
+
 def test_windows_reduce_validation():
     L = gs.lib()
     call = lambda a, win, st, out, op=gs.GS_MAX: L.glenside_windows_reduce(

@@ -466,6 +466,33 @@ def test_pad(case):
     assert_same_values(got, ap.pad(ap.access(ap.tensor(to_oracle(x)), na), dim, lo, hi, fill), str(case))
 
 
+@pytest.mark.parametrize("dtype,block", [("i8", 16), ("i8", 32), ("bf16", 16), ("bf16", 64)])
+def test_cartesian_dot_blocked_is_the_blocked_program(dtype, block):
+    """Square blocks, every dimension a multiple: the program of Fig. 7 generalised, block by block."""
+    m, k, o = 2 * block, 4 * block, 3 * block
+    a = gen(dtype, (m, k), 2701 + block, 1.0)
+    w = gen(dtype, (k, o), 2702 + block, 1.0 / np.sqrt(k) if dtype == "bf16" else 1.0)    # (K,O) as in Fig. 2b
+    wt = gs.transpose(w.to(DEV), 1, (1, 0))                                                 # ((O),(K))
+    got = gs.cartesian_dot_blocked(a.to(DEV), wt, block, block, block)
+    prog, count = pg.blocked_matmul(ap.tensor(to_oracle(a)), ap.tensor(to_oracle(w)), block)
+    assert count == 2 * 3 * 4
+    assert_parity(got, prog.materialize(), what=f"blocked {dtype} {block}")
+    if dtype == "i8":
+        assert torch.equal(got, gs.cartesian_dot(a.to(DEV), wt))
+
+
+@pytest.mark.parametrize("tiles", [(64, 64, 128), (100, 48, 80), (1000, 1000, 1000), (17, 256, 33)])
+def test_cartesian_dot_blocked_ragged_tiles(tiles):
+    """Tile sizes that do not divide the matrix: last blocks and last K slices are smaller."""
+    a0, a1 = gen("i8", (150, 328), 2801), gen("i8", (130, 328), 2802)
+    got = gs.cartesian_dot_blocked(a0.to(DEV), a1.to(DEV), *tiles)
+    assert torch.equal(got, gs.cartesian_dot(a0.to(DEV), a1.to(DEV)))
+    b0, b1 = gen("bf16", (150, 320), 2803), gen("bf16", (130, 320), 2804, 1.0 / np.sqrt(320))
+    gotf = gs.cartesian_dot_blocked(b0.to(DEV), b1.to(DEV), *tiles)
+    prog = pg.cartesian_dot(ap.access(ap.tensor(to_oracle(b0)), 1), ap.access(ap.tensor(to_oracle(b1)), 1))
+    assert_parity(gotf, prog.materialize(), what=f"ragged {tiles}")
+
+
 def test_blocked_matmul_from_slices_and_concat():
     """Fig. 7 on the GPU: a matmul split in two along N and K with slice, cartProd/dotProd on the
     blocks, pair + reduceSum over the K halves and concat along N equals the unblocked product
