@@ -53,7 +53,7 @@ TRAFFIC = {
     "maxpool": (102.99e6 + 25.69e6, "reduce", "9eb204f97458193b5ff9a1e28624d7ce9aa9d701c334204564151583e275147e"),
     "reduce": (268.44e6 + 0.52e6, "reduce", "9eb204f97458193b5ff9a1e28624d7ce9aa9d701c334204564151583e275147e"),
     "transpose": (25.76e6 + 25.70e6, "move", "51ea9bb799d81af55674aeeb70557e247c1f0d9205b92f83666c6b67f5baa81f"),
-    "dense_blocked": (5.65e6 + 1.05e6, "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),
+    "dense_blocked": (64 * (5.65e6 + 1.05e6), "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),       # 64 launches per step, each of one 512^3 block
     "dense": (1635.93e6 + 274.91e6, "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),
     "mlp_scaled": (29.33e6 + 16.78e6, "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),
 }
