@@ -551,7 +551,7 @@ def main():
         "event_ms_per_step": ev_ms / args.steps,
         "roofline": {"bound": bound, "kernel": wl.dominant, "achieved": achieved,
                      "peak": peak, "unit": unit, "frac": achieved / peak,
-                     "us_per_launch": dom_s * 1e6, "traffic": _traffic(args.workload)},
+                     "us_per_launch": dom_s * 1e6, "traffic": None if args.tile not in (None, 512) else _traffic(args.workload)},   # counters were taken at the default tile
     }
     if not args.no_cpu_baseline:
         base = wl.cpu_baseline()
