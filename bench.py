@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 import torch  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_I8_TOPS = 5000.0         # MI355X dense int8 MFMA
 PEAK_HBM_GBS = 8000.0
 ROTATE_BYTES = 512 << 20      # rotate over enough buffer sets to exceed the last-level cache
 DOM_BATCH = 20                # launches of the dominant kernel per timing graph
@@ -106,22 +107,24 @@ class Conv3x3:
     """ResNet-style 3x3 convolution: N=32, C=64, 56x56 -> 64 channels, stride 1, pad 1, bf16."""
 
     batch = 32
+    in_dtype = "bf16"
     dominant = "conv_direct4_kernel"
-    name = property(lambda self: f"resnet-style 3x3 conv N={self.batch} C=64 H=W=56 O=64 s1 p1, "
-                                 "bf16 in/out, fp32 accumulate")
+    name = property(lambda self: f"resnet-style 3x3 conv N={self.batch} C=64 H=W=56 O=64 s1 p1, " +
+                                 ("bf16 in/out, fp32 accumulate" if self.in_dtype == "bf16" else "int8 in, int32 out"))
 
     def __init__(self, dev):
         from paper_2105_09377_amd import binding as gs, synth
         self.gs = gs
-        cfg = synth.resnet_conv3x3("bf16", self.batch)
+        cfg = synth.resnet_conv3x3(self.in_dtype, self.batch)
         self.cfg = cfg
         x, w = cfg["x"], cfg["w"]
         self.flops = 2.0 * self.batch * 56 * 56 * 64 * 64 * 9
-        set_bytes = 2 * x.numel() * 2
+        set_bytes = x.numel() * x.element_size() + x.numel() * (2 if self.in_dtype == "bf16" else 4)
         self.nsets = max(2, min(48, -(-ROTATE_BYTES // set_bytes)))
         self.w = w.to(dev)
         self.xs = [x.to(dev).clone() for _ in range(self.nsets)]
-        self.outs = [torch.empty((self.batch, 64, 56, 56), dtype=torch.bfloat16, device=dev) for _ in range(self.nsets)]
+        out_dtype = torch.bfloat16 if self.in_dtype == "bf16" else torch.int32
+        self.outs = [torch.empty((self.batch, 64, 56, 56), dtype=out_dtype, device=dev) for _ in range(self.nsets)]
         self.ws = torch.empty(gs.conv2d_workspace(self.xs[0], self.w, (1, 1), (1, 1)), dtype=torch.uint8, device=dev)
         self.packed = gs.conv2d_pack_weights(self.w)
 
@@ -148,6 +151,27 @@ class Conv3x3:
         dt = time.perf_counter() - t0
         return {"value": self.flops * n / self.batch / dt / 1e12, "unit": "TFLOP/s", "cores": brute.num_threads(),
                 "kind": "oracle", "sample": f"brute-force C loops (fp64, OpenMP) on {n} images of the workload, {dt:.2f} s"}
+
+
+class Conv3x3Int8(Conv3x3):
+    """The same convolution with int8 inputs and exact int32 results."""
+
+    in_dtype = "i8"
+    dtype = "i8"
+    bound, unit, peak = "mfma", "TOP/s", PEAK_I8_TOPS
+
+    def cpu_baseline(self):
+        import numpy as np
+        from oracle import brute
+        n = 32
+        xo = self.cfg["x"][:n].numpy().astype(np.int64)
+        wo = self.cfg["w"].numpy().astype(np.int64)
+        brute.conv2d(xo[:1], wo, (1, 1), (1, 1))
+        t0 = time.perf_counter()
+        brute.conv2d(xo, wo, (1, 1), (1, 1))
+        dt = time.perf_counter() - t0
+        return {"value": self.flops * n / self.batch / dt / 1e12, "unit": "TOP/s", "cores": brute.num_threads(),
+                "kind": "oracle", "sample": f"brute-force C loops (int64, OpenMP) on {n} images of the workload, {dt:.2f} s"}
 
 
 class Conv3x3Batch64(Conv3x3):
@@ -462,7 +486,7 @@ class MlpScaled(Mlp):
         return None
 
 
-WORKLOADS = {"conv3x3": Conv3x3, "conv3x3_b64": Conv3x3Batch64, "resnet18": ResNet18, "im2col_gather": Im2colGather, "maxpool": MaxPool,
+WORKLOADS = {"conv3x3": Conv3x3, "conv3x3_b64": Conv3x3Batch64, "conv3x3_i8": Conv3x3Int8, "resnet18": ResNet18, "im2col_gather": Im2colGather, "maxpool": MaxPool,
              "reduce": RowReduce, "transpose": Transpose, "dense": DenseBig, "dense_blocked": DenseBlocked, "mlp": Mlp, "mlp_scaled": MlpScaled}
 
 
@@ -534,7 +558,7 @@ def main():
     bound = getattr(wl, "bound", "mfma")
     unit = getattr(wl, "unit", "TFLOP/s")
     peak = getattr(wl, "peak", PEAK_BF16_TFLOPS)
-    scale = 1e12 if unit == "TFLOP/s" else 1e9
+    scale = 1e12 if unit in ("TFLOP/s", "TOP/s") else 1e9
     work = getattr(wl, "work", None) or wl.flops
     dom_work = getattr(wl, "dominant_work", None) or getattr(wl, "dominant_flops", None) or work
     achieved = dom_work / dom_s / scale
