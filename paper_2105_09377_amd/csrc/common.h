@@ -39,6 +39,12 @@ __device__ __forceinline__ void lds_barrier() {
   // global_load_lds transfer (they write LDS), which is exactly what must stay in flight.
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
+// The same barrier from compiler builtins, for code whose LDS reads are ordinary loads: the
+// compiler's wait-count bookkeeping sees this wait and does not repeat it (in full) later.
+__device__ __forceinline__ void lds_barrier_tracked() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0); vmcnt and expcnt at their maxima = no wait
+  __builtin_amdgcn_s_barrier();
+}
 // 16 bytes per lane, global -> LDS, without passing through registers: lane i of the wave lands at
 // lds_base + 16 i (lds_base must be wave-uniform).  Written as asm rather than through the
 // compiler builtin on purpose: the compiler orders every later LDS access after a builtin
@@ -49,6 +55,12 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_base) {
   const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :: "v"(gptr), "s"(base) : "memory", "m0");
+}
+// The same with the source given as a wave-uniform base plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void lds_dma16_off(const void* base, uint32_t byte_off, uint32_t lds_base) {
+  const uint32_t lb = __builtin_amdgcn_readfirstlane(lds_base);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(byte_off), "s"(base), "s"(lb) : "memory", "m0");
 }
 // Wait until at most N of this wave's vector-memory loads (which complete in order) are still
 // outstanding.  N above the counter's range waits for more than necessary, never less.

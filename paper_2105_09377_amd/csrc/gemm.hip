@@ -5,8 +5,10 @@
 // with 16-byte loads and no transposition.  A workgroup of 4 or 8 waves owns a BM x BN output tile
 // (the concat-on-access-dimensions blocking of Sec. 5.4); the K loop walks 128-byte slabs (the
 // pair/reduceSum blocking on the compute dimension), double-buffered in LDS with the next slab's
-// global loads in flight while the current one feeds the MFMAs.  The kernels are written in
-// bytes: a slab row is 128 bytes = 64 bf16 or 128 int8, one MFMA eats 32 bytes of K per row.
+// global loads in flight while the current one feeds the MFMAs; fragment reads run one K step
+// ahead of the MFMAs and the per-slab barrier sits under the slab's last MFMAs.  The kernels are
+// written in bytes: a slab row is 128 bytes = 64 bf16 or 128 int8, one MFMA eats 32 bytes of K
+// per row.
 //
 // Two kernels:
 //   gemm_nt_dma_kernel     : aligned operands, K a whole number of 32-byte MFMA steps (the last
@@ -27,6 +29,8 @@
 #include "common.h"
 
 #include <stdlib.h>
+
+#include <mutex>
 
 namespace gs {
 
@@ -152,23 +156,25 @@ __global__ void __launch_bounds__(256) gemm_nt_checked_kernel(GemmArgs a) {
 
 // ---------------------------------------------------------------------------------------------
 // Direct-to-LDS kernel.  LDS slab layout: row r at r*128 bytes, 16-byte column c of that row at
-// position c ^ (r & 7).  One global_load_lds instruction fills 8 rows: lane i lands at
-// (row i/8, position i%8) and therefore fetches global column (i%8) ^ (i/8).
+// position c ^ ((r / 2) % 8).  One transfer instruction fills 8 rows: lane i lands at
+// (row i/8, position i%8) and therefore fetches global column (i%8) ^ swizzle(row).
 // ---------------------------------------------------------------------------------------------
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
 
-template <typename TR, int BM, int BN, int WGM, int WGN>
+template <typename TR, int BM, int BN, int WGM, int WGN, int SB, int NS>
 __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a) {
   constexpr int NW = WGM * WGN;                   // waves per workgroup
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+  static_assert(SB == 64 || SB == 128, "K bytes per slab row");
+  static_assert(NS >= 2, "slab buffers");
   constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
   constexpr int MI = WM / 32, NJ = WN / 32;       // 32x32 MFMA blocks per wave
-  constexpr int XQ = BM / 8 / NW, YQ = BN / 8 / NW;   // 8-row load instructions per wave per slab
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
-  constexpr int kXBytes = BM * kSlabBytes, kYBytes = BN * kSlabBytes;
-  constexpr int kBuf = kXBytes + kYBytes;
-  constexpr int KS = kSlabBytes / 32;             // MFMA K steps per slab
+  constexpr int C = SB / 16;                      // 16-byte columns per slab row
+  constexpr int RPB = 256 / SB;                   // slab rows per 256 bytes (one pass over the 64 banks)
+  constexpr int RPI = 1024 / SB;                  // slab rows filled by one transfer instruction
+  constexpr int XQ = BM / RPI / NW, YQ = BN / RPI / NW, Q = XQ + YQ;   // transfer instructions per wave and slab
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split over the waves");
+  constexpr int kXBytes = BM * SB, kYBytes = BN * SB;
+  constexpr int KS = SB / 32;                     // MFMA K steps per slab
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -180,41 +186,56 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   const uint8_t* X = static_cast<const uint8_t*>(a.x);
   const uint8_t* Y = static_cast<const uint8_t*>(a.y);
   const int64_t ldxb = a.ldx * TR::kEsz, ldyb = a.ldy * TR::kEsz;
-  // K is a whole number of 32-byte MFMA steps; the last slab may hold fewer than four of them.
+  // K is a whole number of 32-byte MFMA steps; the last slab may hold fewer than KS of them.
   const int64_t Kb = a.K * TR::kEsz;
-  const int nslab = int(ceil_div(Kb, kSlabBytes));
-  const int tail_steps = int((Kb - int64_t(nslab - 1) * kSlabBytes) / 32);   // 1..4 steps in the last slab
+  const int nslab = int(ceil_div(Kb, SB));
+  const int tail_steps = int((Kb - int64_t(nslab - 1) * SB) / 32);   // 1..KS steps in the last slab
 
-  // Global source of each of this lane's load instructions (rows past the end are clamped: their
-  // products land in accumulators that are never stored).
-  const int lrow = lane >> 3, lcol = ((lane & 7) ^ lrow) * 16;
-  const uint8_t* xsrc[XQ];
-  const uint8_t* ysrc[YQ];
+  // LDS slab layout: row r at r * SB bytes, its 16-byte column c at position c ^ swizzle(r) with
+  // swizzle(r) = (r / RPB) % C.  The LDS has 64 four-byte banks and serves a 16-byte read 16 lanes
+  // at a time; the 16 consecutive rows those lanes read in one K step then fall on 16 different
+  // 16-byte bank groups.  A transfer instruction fills RPI consecutive rows: lane i lands at
+  // (row i / C, position i % C) and therefore fetches global column (i % C) ^ swizzle(row).
+  // Rows past the end of an operand are clamped: their products land in accumulators that are
+  // never stored.
+  const int lrow = lane / C;
+  const int lcol = ((lane % C) ^ (((wave * RPI + lrow) / RPB) % C)) * 16;
+  static_assert((NW * RPI / RPB) % C == 0, "the swizzle of a transfer's rows must not depend on q");
+  // Sources are a wave-uniform 64-bit base (the tile's first row, advanced by the slab in scalar
+  // registers) plus a 32-bit byte offset per lane and instruction (the host keeps 256 rows of
+  // either operand below 4 GB).
+  const uint8_t* const xbase = X + i0 * ldxb;
+  const uint8_t* const ybase = Y + j0 * ldyb;
+  uint32_t xoff[XQ], yoff[YQ];
 #pragma unroll
   for (int q = 0; q < XQ; ++q) {
-    int64_t row = i0 + (wave + q * NW) * 8 + lrow;
-    row = row < a.I ? row : a.I - 1;
-    xsrc[q] = X + row * ldxb + lcol;
+    int64_t row = (wave + q * NW) * RPI + lrow;
+    row = i0 + row < a.I ? row : a.I - 1 - i0;
+    xoff[q] = uint32_t(row * ldxb + lcol);
   }
 #pragma unroll
   for (int q = 0; q < YQ; ++q) {
-    int64_t row = j0 + (wave + q * NW) * 8 + lrow;
-    row = row < a.J ? row : a.J - 1;
-    ysrc[q] = Y + row * ldyb + lcol;
+    int64_t row = (wave + q * NW) * RPI + lrow;
+    row = j0 + row < a.J ? row : a.J - 1 - j0;
+    yoff[q] = uint32_t(row * ldyb + lcol);
   }
   // In a short last slab the 16-byte columns past K are not multiplied; their lanes re-read
   // column 0 of the slab instead of running past the end of the row (and of the matrix).
-  const int64_t tail_fix = (((lane & 7) ^ lrow) * 16 >= tail_steps * 32) ? -int64_t(lcol) : 0;
-  auto issue_slab = [&](int slab, int buf) {
-    const int64_t k0 = int64_t(slab) * kSlabBytes + (slab == nslab - 1 ? tail_fix : 0);
-    uint8_t* xs = lds + buf * kBuf + wave * 1024;
-    uint8_t* ys = xs + kXBytes;
-#pragma unroll
-    for (int q = 0; q < XQ; ++q)
-      __builtin_amdgcn_global_load_lds((gptr_t)(xsrc[q] + k0), (lptr_t)(xs + q * NW * 1024), 16, 0, 0);
-#pragma unroll
-    for (int q = 0; q < YQ; ++q)
-      __builtin_amdgcn_global_load_lds((gptr_t)(ysrc[q] + k0), (lptr_t)(ys + q * NW * 1024), 16, 0, 0);
+  const uint32_t tail_fix = (lcol >= tail_steps * 32) ? uint32_t(lcol) : 0u;
+  // LDS: [X buffers 0 .. NS-1 | Y buffers 0 .. NS-1].
+  constexpr int kYBase = NS * kXBytes;
+  static_assert((MI - 1) * 32 * SB < 65536 && (NJ - 1) * 32 * SB < 65536, "blocks by immediate offset");
+  const uint32_t lds0 = lds_addr_of(lds);
+  // Transfer instruction idx (0 .. Q - 1) of slab `slab` into buffer `buf`.
+  auto issue_one = [&](int slab, int buf, auto idx_) {
+    constexpr int idx = decltype(idx_)::value;
+    const int64_t k0 = int64_t(slab) * SB;
+    const uint32_t fix = slab == nslab - 1 ? tail_fix : 0u;
+    if constexpr (idx < XQ)
+      lds_dma16_off(xbase + k0, xoff[idx] - fix, lds0 + buf * kXBytes + (wave + idx * NW) * 1024);
+    else
+      lds_dma16_off(ybase + k0, yoff[idx - XQ] - fix,
+                    lds0 + kYBase + buf * kYBytes + (wave + (idx - XQ) * NW) * 1024);
   };
 
   typename TR::accv_t acc[MI][NJ];
@@ -225,38 +246,116 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
     });
   });
 
-  // Fragment addresses: row (lane % 32) of a 32-row block, column 2*ks + lane/32, swizzled.
-  int koff[KS];
+  // Fragment addresses in the buffer being multiplied: row (lane % 32) of a 32-row block, 16-byte
+  // column 2*ks + lane/32, swizzled; one address register per operand and K step, moved to the
+  // next buffer once per slab; the 32-row blocks of a wave by immediate offset.
+  const uint8_t* xa[KS];
+  const uint8_t* ya[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) koff[ks] = (((2 * ks + (lane >> 5)) ^ (lane & 7)) << 4);
-  const int xrow = (wm * WM + (lane & 31)) * kSlabBytes;
-  const int yrow = kXBytes + (wn * WN + (lane & 31)) * kSlabBytes;
-
-  issue_slab(0, 0);
-  __syncthreads();
-  for (int slab = 0; slab < nslab; ++slab) {
-    if (slab + 1 < nslab) issue_slab(slab + 1, (slab + 1) & 1);
-    const uint8_t* base = lds + (slab & 1) * kBuf;
-    const int steps = slab == nslab - 1 ? tail_steps : KS;
+  for (int ks = 0; ks < KS; ++ks) {
+    const int koff = ((2 * ks + (lane >> 5)) ^ (((lane & 31) / RPB) % C)) << 4;
+    xa[ks] = lds + (wm * WM + (lane & 31)) * SB + koff;
+    ya[ks] = lds + kYBase + (wn * WN + (lane & 31)) * SB + koff;
+  }
+  // The K loop is software-pipelined by hand.  Slabs s+1 .. s+NS-1 are in flight (or landed)
+  // while slab s is multiplied.  The fragments of K step k + 1 are requested before the MFMAs of
+  // step k are issued (two register sets; scheduling barriers keep the compiler from undoing that
+  // order, its own wait-count insertion does the rest), and the workgroup barrier of a slab sits
+  // in front of the MFMAs of its LAST step, so those MFMAs cover the barrier and the latency of
+  // the next slab's first fragments.  At that barrier every wave has (a) received all of its
+  // fragments of the current slab (lgkmcnt 0), so its buffer may be overwritten by slab s+NS, and
+  // (b) waited for its own direct-to-LDS transfers of slab s+1 (vmcnt: the counter belongs to the
+  // issuing wave and transfers complete in order), so after the barrier all of that slab is in LDS.
+  // The fragment reads are ordinary loads, not asm: a register written by an asm read would be
+  // "defined" for the compiler at once, and copies it makes of such a register (across the loop's
+  // back edge, under register pressure) would run before the data has arrived.  The loop bodies
+  // are free of branches (steady state and drain are separate loops) so that the accumulators
+  // stay in place.
+  i32x4 fr[2][MI + NJ];
+  auto request = [&](auto ks_, auto slot_) {
+    constexpr int ks = decltype(ks_)::value, slot = decltype(slot_)::value;
+#pragma unroll
+    for (int m = 0; m < MI; ++m) fr[slot][m] = *reinterpret_cast<const i32x4*>(xa[ks] + m * 32 * SB);
+#pragma unroll
+    for (int n = 0; n < NJ; ++n) fr[slot][MI + n] = *reinterpret_cast<const i32x4*>(ya[ks] + n * 32 * SB);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto multiply = [&](auto slot_) {
+    constexpr int slot = decltype(slot_)::value;
+#pragma unroll
+    for (int m = 0; m < MI; ++m)
+#pragma unroll
+      for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(fr[slot][m], fr[slot][MI + n], acc[m][n]);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  static_assert(KS % 2 == 0, "register sets alternate per K step and restart with every slab");
+  int s = 0, buf = 0;               // slab being multiplied and its buffer (s % NS)
+  // One full slab (another slab follows it).  ISSUE: slab s + NS exists and is requested.
+  auto full_slab = [&](auto issue_) {
+    constexpr bool ISSUE = decltype(issue_)::value;
     static_for<KS>([&](auto ks_) {
       constexpr int ks = decltype(ks_)::value;
-      if (ks < steps) {                              // uniform: only the last slab can be short
-        i32x4 af[MI], bf[NJ];
+      constexpr int slot = ks & 1;
+      if constexpr (ks + 1 < KS) {
+        request(std::integral_constant<int, ks + 1>{}, std::integral_constant<int, slot ^ 1>{});
+        multiply(std::integral_constant<int, slot>{});
+      } else {
+        // slabs s+1 .. min(s+NS-1, last) are outstanding; s+1 must have landed
+        if constexpr (ISSUE) wait_vmem<(NS - 2) * Q>();
+        else wait_vmem<0>();
+        lds_barrier_tracked();         // lgkmcnt(0), then the workgroup barrier
+        const int done_buf = buf;
+        const bool wrap = buf + 1 == NS;
+        buf = wrap ? 0 : buf + 1;
+        const int dx = wrap ? -(NS - 1) * kXBytes : kXBytes, dy = wrap ? -(NS - 1) * kYBytes : kYBytes;
 #pragma unroll
-        for (int m = 0; m < MI; ++m)
-          af[m] = *reinterpret_cast<const i32x4*>(base + xrow + m * 32 * kSlabBytes + koff[ks]);
-#pragma unroll
-        for (int n = 0; n < NJ; ++n)
-          bf[n] = *reinterpret_cast<const i32x4*>(base + yrow + n * 32 * kSlabBytes + koff[ks]);
-#pragma unroll
-        for (int m = 0; m < MI; ++m)
-#pragma unroll
-          for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(af[m], bf[n], acc[m][n]);
+        for (int k = 0; k < KS; ++k) {
+          xa[k] += dx;
+          ya[k] += dy;
+        }
+        request(I0{}, std::integral_constant<int, slot ^ 1>{});
+        // the transfers of slab s + NS, into the buffer just drained, go between this step's MFMAs
+        static_for<(MI * NJ > (ISSUE ? Q : 0) ? MI * NJ : Q)>([&](auto i_) {
+          constexpr int i = decltype(i_)::value;
+          if constexpr (i < MI * NJ) {
+            constexpr int m = i / NJ, n = i % NJ;
+            acc[m][n] = TR::mfma(fr[slot][m], fr[slot][MI + n], acc[m][n]);
+          }
+          if constexpr (ISSUE && i < Q) issue_one(s + NS, done_buf, i_);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        ++s;
       }
     });
-    __syncthreads();   // next slab has landed (the barrier waits for this wave's loads) and
-                       // every wave is done reading the current one
-  }
+  };
+
+  static_for<NS>([&](auto b_) {
+    if (decltype(b_)::value < nslab)
+      static_for<Q>([&](auto idx_) { issue_one(decltype(b_)::value, decltype(b_)::value, idx_); });
+  });
+  // Arguments that only the epilogue reads are fetched here: a scalar load left pending across
+  // the K loop would make every wait for LDS fragments a wait for everything (scalar loads return
+  // out of order on the same counter).
+  asm volatile("" ::"s"(a.relu), "s"(a.vj), "s"(a.jp), "s"(a.residual), "s"(a.out), "s"(a.out_dtype));
+  if (nslab >= NS) wait_vmem<(NS - 1) * Q>();
+  else wait_vmem<0>();
+  lds_barrier_tracked();
+  request(I0{}, I0{});
+  while (s + NS < nslab) full_slab(std::true_type{});     // steady state
+  while (s + 1 < nslab) full_slab(std::false_type{});     // drain: nothing left to request
+  static_for<KS>([&](auto ks_) {    // last slab: 1..KS steps; its first fragments are on their way
+    constexpr int ks = decltype(ks_)::value;
+    constexpr int slot = ks & 1;
+    if (ks < tail_steps) {                         // uniform
+      if constexpr (ks + 1 < KS) {
+        if (ks + 1 < tail_steps)
+          request(std::integral_constant<int, ks + 1>{}, std::integral_constant<int, slot ^ 1>{});
+      }
+      multiply(std::integral_constant<int, slot>{});
+    }
+  });
+  __syncthreads();   // every wave is done with the slabs: their memory becomes epilogue staging
 
   // Epilogue: lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4 of each block.
   // Results larger than the last-level cache are streamed past L2.
@@ -268,7 +367,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   // instruction carries 16 (or 8) bytes per lane instead of one element.
   if (a.vj > 1) {
     constexpr int RS = WN * 4 + 16;                 // staging row stride in bytes
-    static_assert(NW * 32 * RS <= 2 * kBuf, "staging must fit in the slab buffers");
+    static_assert(NW * 32 * RS <= NS * (kXBytes + kYBytes), "staging must fit in the slab buffers");
     uint8_t* stage = lds + wave * (32 * RS);
     const bool has_res = a.residual != nullptr;
     auto write_back = [&](auto vj_, auto kind_) {
@@ -403,17 +502,18 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   });
 }
 
-template <typename TR, int BM, int BN, int WGM, int WGN>
+template <typename TR, int BM, int BN, int WGM, int WGN, int SB, int NS>
 static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
-  constexpr int lds_bytes = 2 * (BM + BN) * kSlabBytes;
-  auto kern = gemm_nt_dma_kernel<TR, BM, BN, WGM, WGN>;
-  static bool attr_done = false;   // benign race: the attribute call is idempotent
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  constexpr int lds_bytes = NS * (BM + BN) * SB;
+  static_assert(lds_bytes <= 160 * 1024, "LDS of a compute unit");
+  auto kern = gemm_nt_dma_kernel<TR, BM, BN, WGM, WGN, SB, NS>;
+  static std::once_flag once;
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(once, [&]() {
+    attr_status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const int64_t tiles = ceil_div(a.I, BM) * ceil_div(a.J, BN);
   hipLaunchKernelGGL(kern, dim3(unsigned(tiles)), dim3(WGM * WGN * 64), lds_bytes, s, a);
   return hipGetLastError();
@@ -424,11 +524,11 @@ template <typename TR>
 static hipError_t launch_dma_tiles(const GemmArgs& a, hipStream_t s) {
   const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
   const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);
-  if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4>(a, s);
+  if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4, 128, 2>(a, s);
   // few rows (a convolution's output channels against many positions): tiles 64 rows tall
-  if (a.I <= 64 && ceil_div(a.J, 256) >= 192) return launch_dma<TR, 64, 256, 1, 4>(a, s);
-  if (t128 >= 192) return launch_dma<TR, 128, 128, 2, 2>(a, s);
-  return launch_dma<TR, 64, 64, 2, 2>(a, s);
+  if (a.I <= 64 && ceil_div(a.J, 256) >= 192) return launch_dma<TR, 64, 256, 1, 4, 128, 2>(a, s);
+  if (t128 >= 192) return launch_dma<TR, 128, 128, 2, 2, 128, 2>(a, s);
+  return launch_dma<TR, 64, 64, 2, 2, 128, 2>(a, s);
 }
 
 template <typename TR>
@@ -436,7 +536,9 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
   const bool vec = (a.ldx * TR::kEsz) % 16 == 0 && (a.ldy * TR::kEsz) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.x) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.y) % 16 == 0;
-  const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % 32 == 0;   // whole MFMA steps
+  // whole MFMA steps, and 256 rows of either operand within reach of a 32-bit byte offset
+  const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % 32 == 0 && a.ldx * TR::kEsz < (int64_t(1) << 23) &&
+                   a.ldy * TR::kEsz < (int64_t(1) << 23);
   if (dma) {
     // Columns per lane of the vector write-back: groups of vj columns must not straddle a jp
     // boundary or the end of the result, and must be 16-byte (8-byte for 4 bfloat16) aligned.

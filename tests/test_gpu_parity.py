@@ -141,6 +141,53 @@ def test_cartesian_dot_empty():
     a1 = torch.zeros((8, 16), dtype=torch.bfloat16, device=DEV)
     assert gs.cartesian_dot(a0, a1).shape == (0, 8)
 
+# Products large enough for the 256x256 (8 waves) and 128x128 tiles of the direct-to-LDS kernel,
+# with ragged last tiles in both directions and results written 8, 4 and 1 columns per lane.
+# Sampled rows of a0 (first, last, and both sides of tile boundaries) against every row of a1.
+BIG_DOT_CASES = [
+    # dtype, I, J, K, out dtype, relu
+    ("bf16", 4100, 4104, 512, torch.bfloat16, True),     # 256x256, 8 columns per lane
+    ("bf16", 4100, 4100, 512, torch.float32, False),     # 256x256, 4 columns per lane
+    ("bf16", 4099, 4099, 144, torch.bfloat16, False),    # 256x256, one column per lane, short last slab
+    ("i8", 4100, 4104, 512, torch.int32, True),          # 256x256 int8
+    ("i8", 4100, 4099, 96, torch.int32, False),
+    ("bf16", 1800, 1808, 264 * 2, torch.bfloat16, True), # 128x128, 8 columns per lane
+    ("bf16", 1800, 1804, 264 * 2, torch.float32, False), # 128x128, 4 columns per lane
+    ("i8", 1801, 1803, 160, torch.int32, False),         # 128x128, one column per lane
+    ("i8", 1800, 1808, 512, torch.int32, True),
+]
+
+
+@pytest.mark.parametrize("case", BIG_DOT_CASES)
+def test_cartesian_dot_large_tiles(case):
+    dtype, I, J, K, odt, relu = case
+    a0 = gen(dtype, (I, K), 1400 + I + K, 1.0)
+    a1 = gen(dtype, (J, K), 1500 + J + K, 1.0 / np.sqrt(K) if dtype == "bf16" else 1.0)
+    got = gs.cartesian_dot(a0.to(DEV), a1.to(DEV), 1, 1, odt, gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE)
+    rows = sorted({0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, 257, 1023, 1024, I // 2, I - 130, I - 5, I - 2, I - 1}
+                  | set(int(v) for v in np.random.default_rng(I + J).integers(0, I, 40)))
+    idx = torch.tensor(rows)
+    want = brute.matmul(to_oracle(a0[idx]), to_oracle(a1).T)
+    if relu:
+        want = np.maximum(want, 0)
+    assert_parity(got[idx.to(DEV)], want, what=str(case))
+
+
+@pytest.mark.parametrize("dtype,odt", [("bf16", torch.bfloat16), ("bf16", torch.float32), ("i8", torch.int32)])
+@pytest.mark.parametrize("o,n", [(256, 21), (128, 8), (192, 24)])
+def test_conv2d_im2col_large_tiles_residual_relu(dtype, odt, o, n):
+    """1x1 convolutions whose im2col product takes the 256x256 (O = 256, 65856 positions; O = 192
+    with a ragged channel tile) and 128x128 (O = 128, 25088 positions) tiles, with the fused
+    residual and ReLU and the (N,O,H',W') addressing of the stores; whole images."""
+    cfg = synth.conv_layer(n, 64, 56, 56, o, 1, 1, 0, dtype, 8100 + o + n, gain=1.0)
+    res = gen("i32" if dtype == "i8" else ("bf16" if odt == torch.bfloat16 else "f32"), (n, o, 56, 56), 8200 + o)
+    got = gs.conv2d_im2col(cfg["x"].to(DEV), cfg["w"].to(DEV), (1, 1), (0, 0), residual=res.to(DEV),
+                           act=gs.GS_ACT_RELU, out_dtype=odt)
+    idx = torch.tensor([0, n // 2, n - 1])
+    want = brute.conv2d(to_oracle(cfg["x"][idx]), to_oracle(cfg["w"]), (1, 1), (0, 0)) + to_oracle(res[idx])
+    assert_parity(got[idx.to(DEV)], np.maximum(want, 0), what=f"{dtype} O={o} N={n}")
+
+
 
 # ---------------------------------------------------------------------------------------------
 # conv2d, both forms

@@ -6,6 +6,7 @@ equations, closed forms, special cases with a textbook answer, and numpy library
 """
 
 import itertools
+import math
 
 import numpy as np
 import pytest
@@ -196,6 +197,23 @@ def test_reduce_sum_pins():
     np.testing.assert_array_equal(brute.row_reduce(X, False), X.sum(axis=1))
     np.testing.assert_array_equal(brute.row_reduce(X, True), X.max(axis=1))
     np.testing.assert_array_equal(ap.compute(ap.reduceMax, ap.access(ap.tensor(X), 1)).materialize(), X.max(axis=1))
+    # the real-valued instance of the same loops: closed forms, then random rows against an
+    # exactly rounded sum (math.fsum) and numpy's max
+    ones_f = np.ones((5, 1024), dtype=np.float64)
+    np.testing.assert_array_equal(brute.row_reduce(ones_f, False), np.full(5, 1024.0))
+    ramp = np.tile(np.arange(1.0, 101.0), (3, 1)) * np.array([[1.0], [-1.0], [0.5]])
+    np.testing.assert_array_equal(brute.row_reduce(ramp, False), [5050.0, -5050.0, 2525.0])
+    np.testing.assert_array_equal(brute.row_reduce(ramp, True), [100.0, -1.0, 50.0])
+    F = r.standard_normal((9, 257)) * 10.0 ** r.integers(-3, 4, (9, 257))
+    exact = np.array([math.fsum(row) for row in F])
+    got_f = brute.row_reduce(F, False)
+    assert np.abs(got_f - exact).max() <= 257 * 2.0 ** -52 * np.abs(F).sum(axis=1).max()
+    np.testing.assert_array_equal(brute.row_reduce(F, True), F.max(axis=1))
+    neg = -np.abs(F) - 1.0                                    # a max that must not start from zero
+    np.testing.assert_array_equal(brute.row_reduce(neg, True), neg.max(axis=1))
+    assert brute.row_reduce(np.zeros((4, 0)), False).tolist() == [0.0] * 4   # empty sum
+    with pytest.raises(ValueError):
+        brute.row_reduce(np.zeros((4, 0)), True)              # max of nothing
 
 
 def test_transformer_values():
