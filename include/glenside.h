@@ -144,6 +144,22 @@ size_t glenside_conv2d_direct_workspace(const gs_ap* activations, const gs_ap* w
 size_t glenside_conv2d_im2col_workspace(const gs_ap* activations, const gs_ap* weights,
                                         const int64_t stride[2], const int64_t pad[2]);
 
+/* glenside_conv2d_direct for callers that cannot allocate or pass a workspace (code under HIP
+ * graph capture, serving loops, harnesses that forbid allocation): same arguments without the
+ * workspace, same kernels, same result bit for bit.  The packed weights and the partial sums of
+ * a split channel sum go to a fixed array of glenside_conv2d_direct_static_limit() bytes (32 MiB)
+ * of device memory inside the loaded library, one copy per GPU, held until the process ends.
+ * The call allocates and frees nothing.  A convolution whose glenside_conv2d_direct_workspace
+ * exceeds the limit returns GS_ERR_WORKSPACE and launches nothing.  The array keeps the previous
+ * call's contents and every call on a GPU uses the same one (each call rewrites all it reads), so
+ * calls that overlap in time on one GPU -- different streams, or graphs replayed concurrently --
+ * race; calls on one stream are ordered.  The first call on a GPU looks up the array's device
+ * address (no allocation; make that call outside a capture).                                     */
+int glenside_conv2d_direct_static(const gs_ap* activations, const gs_ap* weights, const int64_t stride[2],
+                                  const int64_t pad[2], const gs_ap* residual, int act, gs_ap* out,
+                                  void* stream);
+size_t glenside_conv2d_direct_static_limit(void);
+
 /* `compute reduceSum | reduceMax` (Table 2): in ((a..),(c..)) -> out ((a..),()).
  * Types: i8 -> i32 (sum) or i8 (max); i32 -> i32; bf16 -> bf16 or f32; f32 -> f32.  Float sums
  * accumulate in fp32.  EXT: scale multiplies a float result (1.0f = the paper's operator; must

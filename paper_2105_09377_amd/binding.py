@@ -34,6 +34,7 @@ EXPORTS = (
     "glenside_windows_reduce", "glenside_pair_reduce", "glenside_conv2d_pack_weights",
     "glenside_conv2d_direct_packed", "glenside_transpose", "glenside_slice", "glenside_concat",
     "glenside_pad", "glenside_pair", "glenside_cartesian_dot_blocked",
+    "glenside_conv2d_direct_static", "glenside_conv2d_direct_static_limit",
 )
 
 
@@ -71,6 +72,9 @@ def lib() -> ctypes.CDLL:
         for f in (L.glenside_conv2d_direct_workspace, L.glenside_conv2d_im2col_workspace):
             f.restype = ctypes.c_size_t
             f.argtypes = [ap_p, ap_p, i64_p, i64_p]
+        L.glenside_conv2d_direct_static.argtypes = [ap_p, ap_p, i64_p, i64_p, ap_p, ctypes.c_int, ap_p, vp]
+        L.glenside_conv2d_direct_static_limit.restype = ctypes.c_size_t
+        L.glenside_conv2d_direct_static_limit.argtypes = []
         L.glenside_conv2d_pack_weights.argtypes = [ap_p, vp, ctypes.c_size_t, vp]
         L.glenside_conv2d_direct_packed.argtypes = conv
         L.glenside_reduce.argtypes = [ap_p, ctypes.c_int, ctypes.c_float, ap_p, vp]
@@ -177,9 +181,10 @@ def _conv(fn_name: str, ws_name: str, x, w, stride, pad, residual, act, out_dtyp
     if out is None:
         if out_dtype is None:
             out_dtype = torch.int32 if x.dtype == torch.int8 else torch.float32
-        ho = (x.shape[2] + 2 * pad[0] - w.shape[2]) // stride[0] + 1
-        wo = (x.shape[3] + 2 * pad[1] - w.shape[3]) // stride[1] + 1
-        out = torch.empty((x.shape[0], w.shape[0], ho, wo), dtype=out_dtype, device=x.device)
+        # H', W' from the library's shape rule of `windows` (window (C,Kh,Kw), strides (1,Sh,Sw))
+        shape, _ = windows_out_shape(x.shape, 1, (x.shape[1], w.shape[2], w.shape[3]), (1, stride[0], stride[1]),
+                                     (0, pad[0], pad[1]), (0, pad[0], pad[1]))
+        out = torch.empty((x.shape[0], w.shape[0], shape[2], shape[3]), dtype=out_dtype, device=x.device)
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
     res = ctypes.byref(make_ap(residual, residual.dim())) if residual is not None else None
@@ -203,6 +208,28 @@ def conv2d_direct(x, w, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NON
     """Fig. 2a with the windows formed on chip; x (N,C,H,W), w (O,C,Kh,Kw) -> (N,O,H',W')."""
     return _conv("glenside_conv2d_direct", "glenside_conv2d_direct_workspace", x, w, stride, pad,
                  residual, act, out_dtype, out, workspace)
+
+
+def conv2d_direct_static(x, w, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NONE, out_dtype=None,
+                         out=None) -> torch.Tensor:
+    """`conv2d_direct` on the library's fixed scratch array: no workspace, nothing allocated by the
+    call (pass `out` to keep torch from allocating the result either)."""
+    if out is None:
+        if out_dtype is None:
+            out_dtype = torch.int32 if x.dtype == torch.int8 else torch.float32
+        shape, _ = windows_out_shape(x.shape, 1, (x.shape[1], w.shape[2], w.shape[3]), (1, stride[0], stride[1]),
+                                     (0, pad[0], pad[1]), (0, pad[0], pad[1]))
+        out = torch.empty((x.shape[0], w.shape[0], shape[2], shape[3]), dtype=out_dtype, device=x.device)
+    res = ctypes.byref(make_ap(residual, residual.dim())) if residual is not None else None
+    _check(lib().glenside_conv2d_direct_static(ctypes.byref(make_ap(x, 1)), ctypes.byref(make_ap(w, 1)),
+                                               _i64(stride), _i64(pad), res, act,
+                                               ctypes.byref(make_ap(out, 4)), _stream(x)),
+           "conv2d_direct_static")
+    return out
+
+
+def conv2d_direct_static_limit() -> int:
+    return int(lib().glenside_conv2d_direct_static_limit())
 
 
 def conv2d_pack_weights(w: torch.Tensor, packed: Optional[torch.Tensor] = None,

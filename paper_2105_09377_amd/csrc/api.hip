@@ -6,6 +6,8 @@
 #include <limits.h>
 #include <string.h>
 
+#include <mutex>
+
 using namespace gs;
 
 namespace {
@@ -399,6 +401,56 @@ int glenside_conv2d_direct(const gs_ap* act, const gs_ap* w, const int64_t strid
   if (st) return st;
   return glenside_conv2d_direct_packed(act, w, stride, pad, residual, actfn, out, workspace,
                                        workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Scratch of glenside_conv2d_direct_static: the packed weights and the partial sums of a split
+// channel sum, in device memory that belongs to the loaded library (one copy per GPU, held until
+// the process ends) instead of memory the caller or the library allocates.
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void* scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up once
+
+// Device address of the array on the current GPU.  The array's name is only a host-side handle:
+// kernels and copies get this pointer.
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GS_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GS_ERR_LAUNCH;
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return GS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t glenside_conv2d_direct_static_limit(void) { return kStaticScratchBytes; }
+
+int glenside_conv2d_direct_static(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                                  const int64_t pad[2], const gs_ap* residual, int actfn,
+                                  gs_ap* out, void* stream) {
+  ConvShape cs;
+  int st = conv_shape(act, w, stride, pad, &cs);
+  if (st) return st;
+  st = conv_check_io(act, w, residual, actfn, out, cs);
+  if (st) return st;
+  if (glenside_conv2d_direct_workspace(act, w, stride, pad) > kStaticScratchBytes) return GS_ERR_WORKSPACE;
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st) return st;
+  return glenside_conv2d_direct(act, w, stride, pad, residual, actfn, out, ws, kStaticScratchBytes, stream);
 }
 
 int glenside_conv2d_im2col(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
