@@ -274,6 +274,7 @@ static hipError_t launch_conv_t(const ConvArgs& a_in, hipStream_t s) {
   g.pair_ok = (a.W % 2 == 0) ? 1 : 0;
   g.max_rows = 0;
   g.tps = 0;
+  g.rb_shift = 0;
   g.dHWo = FastDiv::make(uint32_t(g.HWo > 0 ? g.HWo : 1));
   g.dWo = FastDiv::make(uint32_t(a.Wo > 0 ? a.Wo : 1));
   if (g.M == 0 || a.O == 0) return hipSuccess;

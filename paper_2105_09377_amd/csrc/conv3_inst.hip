@@ -74,6 +74,8 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   const int ksplit = a.ksplit > 1 ? a.ksplit : 1;
   const int nchunk = a.Cpad / (32 / TR::kEsz);
   if (nchunk % (2 * ksplit) != 0) return hipErrorInvalidValue;   // the ring holds two or four chunks
+  // the producers address the packed weights by 32-bit byte offsets
+  if (int64_t(a.O) * a.Kh * a.Kw * a.Cpad * TR::kEsz >= (int64_t(1) << 32)) return hipErrorInvalidValue;
   // Positions per tile: TP, or fewer (in steps that keep each wave's share a multiple of 4) when
   // that lowers rounds x tile cost, a tile's cost being half fixed (the MFMA blocks stay TP wide)
   // and half proportional to its positions (patch traffic, write-back).  Only where that
@@ -89,6 +91,9 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   }
   g.max_rows = conv_max_rows(a, g.M, g.HWo, g.tps);
   if (g.max_rows < 0) return hipErrorInvalidValue;
+  // Patch row pitch: g.PW pixels of 48 bytes with g.PW * 3 / 2 odd, so that consecutive patch rows
+  // of one pixel column fall on different 16-byte bank groups (the producers' LDS stores).
+  while ((g.PW * 3 / 2) % 2 == 0) g.PW += 2;
   const size_t stage_bytes = 4 * 32 * size_t(TP / WP * 4 + 16);   // epilogue staging, one region per wave
   const size_t patch_bytes = 2 * size_t(g.max_rows) * g.PW * 48;
   const size_t lds_bytes = 1024 + NWB * size_t(a.Kh * a.Kw) * TO * 32 + patch_bytes + stage_bytes;
@@ -98,16 +103,26 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   // one row, W a multiple of VW) are tried narrowest first, which keeps the most lanes busy; then
   // items of 4 or 8 pixels consecutive in memory, which cross row ends and need no alignment;
   // then two items per thread.
+  // Aligned items come in blocks of 2^rb_shift patch rows (see the kernel): the largest block
+  // of up to 8 rows whose padding still leaves one item per thread.
+  auto items_rb = [&](int vw, int sh) { return ((int64_t(g.max_rows) + (1 << sh) - 1) >> sh << sh) * (a.W / vw) * 2; };
+  auto pick_rb = [&](int vw, int maxi) {
+    for (int sh = 3; sh > 0; --sh)
+      if (items_rb(vw, sh) <= 192 * maxi) return sh;
+    return 0;
+  };
   auto items = [&](int vw) { return int64_t(g.max_rows) * (a.W / vw) * 2; };
   // Every segment of a tile (one per image it touches) may end with a partial flat item per
   // channel group.
   const int64_t segs = (g.tps + g.HWo - 2) / g.HWo + 1;
   auto flat_items = [&](int vw) { return 2 * ((int64_t(g.max_rows) * a.W + vw - 1) / vw + segs); };
 #define GS_TRY(VW_, MAXI_)                                                                   \
-  if (a.W % VW_ == 0 && items(VW_) <= 256 * MAXI_)                                          \
-    return launch_conv4_cfg<TR, TO, TP, WO, WP, VW_, KH, KW, MAXI_>(a, g, lds_bytes, s);
+  if (a.W % VW_ == 0 && items(VW_) <= 192 * MAXI_) {                                        \
+    g.rb_shift = pick_rb(VW_, MAXI_);                                                        \
+    return launch_conv4_cfg<TR, TO, TP, WO, WP, VW_, KH, KW, MAXI_>(a, g, lds_bytes, s);      \
+  }
 #define GS_TRY_FLAT(VW_, MAXI_)                                                              \
-  if (a.W >= VW_ && flat_items(VW_) <= 256 * MAXI_)                                         \
+  if (a.W >= VW_ && flat_items(VW_) <= 192 * MAXI_)                                         \
     return launch_conv4_cfg<TR, TO, TP, WO, WP, VW_, KH, KW, MAXI_, true>(a, g, lds_bytes, s);
   GS_TRY(1, 1) GS_TRY(2, 1) GS_TRY(4, 1) GS_TRY(8, 1)
   GS_TRY_FLAT(4, 1) GS_TRY_FLAT(8, 1)

@@ -141,44 +141,78 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     // =========================================================================================
     // Producers.  Three cursors walk the same sequence of (tile, chunk) units, each a fixed
     // distance ahead of the consumers: stores 1 unit, weight transfers NWB - 1 units, patch loads
-    // 1 + D units.  Crossing into the next tile only means rebuilding that cursor's descriptors.
+    // 1 + D units.  Everything that depends on the tile only (item sources and destinations,
+    // weight rows, rows to clear) is worked out once, when the load cursor enters the tile, and
+    // handed down to the other cursors; a chunk step itself is loads at a scalar base plus fixed
+    // per-lane offsets, byte permutes, LDS stores at immediate offsets and a few scalar updates.
     // =========================================================================================
-    const int ptid = tid - 256, pwave = wave - 4;
+    // Wave 4 moves the weights; waves 5-7 move the patches (192 threads, numbered by ptid).  A
+    // wave's vector-memory operations complete in order on one counter, so a wave that waited for
+    // its weight transfers would also wait for every patch load it issued before them: with the
+    // roles apart, patch loads keep the whole ring depth to arrive.
+    const int pwave = wave - 4;
+    const int ptid = tid - 320;
+    constexpr int PT = 192;                             // patch threads
     const uint8_t* act = static_cast<const uint8_t*>(a.act);
     const uint8_t* wr = static_cast<const uint8_t*>(a.wr);
     const int64_t plane = int64_t(a.H) * a.W * ESZ;     // bytes per channel plane
     const int64_t wr_row = int64_t(T) * a.Cpad * ESZ;   // bytes per output channel in wr
     const int XGn = a.W / VW;                           // pixel groups per row
     const FastDiv dXG = FastDiv::make(uint32_t(XGn));
-    const FastDiv dPW = FastDiv::make(uint32_t(g.PW));
     const int n_wq = T * OB;
-
-    struct Cursor {
-      int tile, chunk;
-    };
+    const int64_t chunk_bytes = int64_t(CCH) * plane;   // activations: one chunk further
     constexpr int ND = FLAT ? VW : 1;                   // LDS destinations kept per item
     const FastDiv dW = FastDiv::make(uint32_t(a.W));
-    struct Items {
-      const uint8_t* src[MAXI];
-      int dst[MAXI][ND];
-      uint32_t okbits;          // bit i: item i exists
+    const int pl_off = int(pl - lds);
+
+    // Patch items of a tile, per thread.  The tensors have fewer than 2^31 elements (host check),
+    // so byte offsets from the tensor's start fit 32 bits.
+    struct Loads {
+      uint32_t off[MAXI][G];    // item i, channel t of the group: byte offset within the chunk
     };
-    auto make_items = [&](int tile_, Items& it) {
+    struct Stores {
+      int dst[2][MAXI][ND];     // LDS byte offset per patch buffer; the dummy area if the item does not exist
+      int m0, mend;             // the tile's positions (for the rows to clear)
+    };
+    // Aligned items (VW pixels of one row): what does not depend on the tile.  Item id is
+    // (pixel group, block of g.rb patch rows, row within the block, channel group) with the last
+    // two running fastest, so that the 16 lanes an LDS store serves together write rows of one
+    // pixel column: the row pitch (g.PW pixels of 48 bytes, g.PW * 3 / 2 odd) puts eight
+    // consecutive rows on eight different even 16-byte bank groups and the channel group on the
+    // odd ones.  (Lanes along a row, 8 pixels = 384 bytes apart, would share two bank groups.)
+    int item_r[MAXI], item_dst[MAXI];
+    uint32_t item_koff[MAXI];
+    if constexpr (!FLAT) {
+      const int rb_shift = g.rb_shift;
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        const int id = ptid + PT * i;
+        const int cg = id & 1, q = id >> 1;
+        const int q2 = q >> rb_shift;
+        const int r_hi = int(dXG.div(uint32_t(q2))), xg = q2 - r_hi * XGn;
+        item_r[i] = (r_hi << rb_shift) + (q & ((1 << rb_shift) - 1));
+        item_dst[i] = pl_off + (item_r[i] * g.PW + g.XO + xg * VW) * PIXB + cg * 16;
+        item_koff[i] = uint32_t(cg * G) * uint32_t(plane) + uint32_t(xg * VW * ESZ);
+      }
+    }
+    auto make_items = [&](int tile_, Loads& lo, Stores& so) {
       int m0_, mend_, o0_;
       tile_range(tile_, &m0_, &mend_, &o0_);
       const TileSegs ts = tile_segs(m0_, mend_, g);
-      it.okbits = 0;
+      so.m0 = m0_;
+      so.mend = mend_;
       if constexpr (FLAT) {
         // Segment s contributes ceil(L / VW) items per channel group, L = pixels of its valid
         // rows; the last item of a range is moved back to end with the range (it overlaps its
         // neighbour, which is written twice with the same data) so that no load leaves the range.
 #pragma unroll
         for (int i = 0; i < MAXI; ++i) {
-          it.src[i] = act;
+          uint32_t off0 = 0;
+          int dst[ND];
 #pragma unroll
-          for (int e = 0; e < ND; ++e) it.dst[i][e] = 512 + e * PIXB;   // dummy area
-          int rem = ptid + 256 * i, base = 0;
+          for (int e = 0; e < ND; ++e) dst[e] = 512 + e * PIXB;   // dummy area
           bool found = false;
+          int rem = ptid + PT * i, base = 0;
           for (int s_ = 0; s_ < ts.nseg; ++s_) {
             int ihlo, rows;
             seg_extent(ts, s_, g, a.Sh, a.Ph, a.Kh, &ihlo, &rows);
@@ -190,122 +224,145 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
               found = true;
               const int cg = rem >= cnt ? 1 : 0, k = rem - cg * cnt;
               const int f0 = vlo * a.W + (k * VW < L - VW ? k * VW : L - VW);
-              it.okbits |= 1u << i;
-              it.src[i] = act + (int64_t(ts.n_first + s_) * a.C + cg * G) * plane + int64_t(f0) * ESZ;
+              off0 = uint32_t((int64_t(ts.n_first + s_) * a.C + cg * G) * plane + int64_t(f0) * ESZ);
 #pragma unroll
               for (int e = 0; e < ND; ++e) {
                 const int row = int(dW.div(uint32_t(f0 + e))), col = f0 + e - row * a.W;
-                it.dst[i][e] = int(pl - lds) + ((base + row - ihlo) * g.PW + g.XO + col) * PIXB + cg * 16;
+                dst[e] = pl_off + ((base + row - ihlo) * g.PW + g.XO + col) * PIXB + cg * 16;
               }
             }
             rem -= 2 * cnt;
             base += rows;
           }
+#pragma unroll
+          for (int t = 0; t < G; ++t) lo.off[i][t] = off0 + uint32_t(t * plane);
+#pragma unroll
+          for (int e = 0; e < ND; ++e) {
+            so.dst[0][i][e] = dst[e];
+            so.dst[1][i][e] = dst[e] + (found ? pbytes : 0);
+          }
         }
         return;
-      }
+      } else {
+        // One segment (the tile lies within one image): patch row r is input row ihlo + r.
+        int ihlo1 = 0, rows1 = 0;
+        if (ts.nseg == 1) seg_extent(ts, 0, g, a.Sh, a.Ph, a.Kh, &ihlo1, &rows1);
+        const uint32_t img1 = uint32_t(ts.n_first) * uint32_t(a.C) * uint32_t(plane);
 #pragma unroll
-      for (int i = 0; i < MAXI; ++i) {
-        const int id = ptid + 256 * i;
-        it.src[i] = act;
-        it.dst[i][0] = 512;       // dummy area (VW * 48 bytes at most)
-        const int rc = int(dXG.div(uint32_t(id))), xg = id - rc * XGn;
-        const int cg = rc & 1, r = rc >> 1;
-        int s, ih;
-        if (seg_of_row(ts, r, g, a.Sh, a.Ph, a.Kh, &s, &ih) && ih >= 0 && ih < a.H) {
-          it.okbits |= 1u << i;
-          it.src[i] = act + (int64_t(ts.n_first + s) * a.C + cg * G) * plane +
-                      (int64_t(ih) * a.W + xg * VW) * ESZ;
-          it.dst[i][0] = int(pl - lds) + (r * g.PW + g.XO + xg * VW) * PIXB + cg * 16;
+        for (int i = 0; i < MAXI; ++i) {
+          uint32_t off0 = 0;
+          bool ok = false;
+          if (ts.nseg == 1) {                       // uniform
+            const int ih = ihlo1 + item_r[i];
+            ok = item_r[i] < rows1 && ih >= 0 && ih < a.H;
+            off0 = item_koff[i] + img1 + uint32_t(ih) * uint32_t(a.W * ESZ);
+          } else {
+            int s_, ih;
+            if (seg_of_row(ts, item_r[i], g, a.Sh, a.Ph, a.Kh, &s_, &ih) && ih >= 0 && ih < a.H) {
+              ok = true;
+              off0 = item_koff[i] + uint32_t(ts.n_first + s_) * uint32_t(a.C) * uint32_t(plane) +
+                     uint32_t(ih) * uint32_t(a.W * ESZ);
+            }
+          }
+          off0 = ok ? off0 : 0u;
+#pragma unroll
+          for (int t = 0; t < G; ++t) lo.off[i][t] = off0 + uint32_t(t) * uint32_t(plane);
+          so.dst[0][i][0] = ok ? item_dst[i] : 512;            // else the dummy area (VW * 48 bytes at most)
+          so.dst[1][i][0] = ok ? item_dst[i] + pbytes : 512;
         }
       }
     };
     // Rows of a tile's patch that lie outside their image (top / bottom padding) must read as
     // zeros; a row index may have held data of the previous tile, so they are cleared per tile
-    // and buffer.  Data rows are overwritten in full and need no clearing.
-    auto zero_invalid_rows = [&](int tile_, int buf) {
-      int m0_, mend_, o0_;
-      tile_range(tile_, &m0_, &mend_, &o0_);
-      const TileSegs ts = tile_segs(m0_, mend_, g);
-      bool any = false;                                   // uniform: most tiles have none
+    // and buffer.  Data rows are overwritten in full and need no clearing.  The rows outside are
+    // the first -ihlo and the last ihlo + rows - H rows of a segment: thread t clears pixel t.
+    auto zero_invalid_rows = [&](const Stores& so, int buf) {
+      const TileSegs ts = tile_segs(so.m0, so.mend, g);
+      int base = 0;
       for (int s_ = 0; s_ < ts.nseg; ++s_) {
         int ihlo, rows;
         seg_extent(ts, s_, g, a.Sh, a.Ph, a.Kh, &ihlo, &rows);
-        any = any || ihlo < 0 || ihlo + rows > a.H;
-      }
-      if (!any) return;
-      const i32x4 z = {0, 0, 0, 0};
-      for (int id = ptid; id < g.max_rows * g.PW; id += 256) {
-        const int r = int(dPW.div(uint32_t(id)));
-        int s, ih;
-        if (seg_of_row(ts, r, g, a.Sh, a.Ph, a.Kh, &s, &ih) && (ih < 0 || ih >= a.H)) {
-          uint8_t* p = pl + buf * pbytes + id * PIXB;
-          *reinterpret_cast<i32x4*>(p) = z;
-          *reinterpret_cast<i32x4*>(p + 16) = z;
+        const int ntop = ihlo < 0 ? (-ihlo < rows ? -ihlo : rows) : 0;
+        const int nbot = ihlo + rows > a.H ? (ihlo + rows - a.H < rows ? ihlo + rows - a.H : rows) : 0;
+        for (int k = 0; k < ntop + nbot; ++k) {             // uniform; usually no iteration at all
+          const int r = base + (k < ntop ? k : rows - nbot + (k - ntop));
+          for (int x = ptid; x < g.PW; x += PT) {
+            uint8_t* p = pl + buf * pbytes + (r * g.PW + x) * PIXB;
+            const i32x4 z = {0, 0, 0, 0};
+            *reinterpret_cast<i32x4*>(p) = z;
+            *reinterpret_cast<i32x4*>(p + 16) = z;
+          }
         }
+        base += rows;
       }
     };
-    // Weight DMA sources of this lane for output-channel tile o0: instruction q covers tap
-    // q / OB, rows (q % OB) * 32 .. + 31; lane i fills (row i / 2, position i % 2).
+    // Weight transfers: instruction q of a chunk covers tap q / OB, rows (q % OB) * 32 .. + 31 of
+    // the channel tile; lane i fills (row i / 2, position i % 2).  With static taps the per-lane
+    // byte offsets of all of them are fixed per channel tile.
     const int wrow = lane >> 1;
     const int wcol = ((lane & 1) ^ (((wrow >> 2) ^ (wrow >> 3)) & 1)) * 16;
-    struct WSrc { const uint8_t* p[OB]; };
+    constexpr int NWI = KH > 0 ? KH * KW * OB : 0;             // weight instructions per chunk (static taps)
+    struct WSrc {
+      uint32_t off[KH > 0 ? NWI : OB];   // static taps: per instruction; else per 32-row block
+    };
     auto make_wsrc = [&](int tile_, WSrc& w) {
       int m0_, mend_, o0_;
       tile_range(tile_, &m0_, &mend_, &o0_);
-#pragma unroll
-      for (int b = 0; b < OB; ++b) {
-        int o = o0_ + b * 32 + wrow;
-        o = o < a.O ? o : a.O - 1;                      // rows past O are never stored
-        w.p[b] = wr + o * wr_row + wcol;
-      }
-    };
-    constexpr int NWI = KH > 0 ? (KH * KW * OB + 3) / 4 : 0;   // weight instructions per wave and chunk
-    // The descriptors are switched by assignment when a cursor enters a tile; selecting between
-    // two structures per use would make the compiler keep them in scratch memory, whose loads
-    // share the counter that tracks the prefetched global loads.
-    WSrc wld;
-    const uint32_t wl_addr = lds_addr_of(wl);
-    auto issue_weights = [&](int item, int chunk, int slot) {
-      const int64_t coff = int64_t((lg(item) & (ksplit - 1)) * nchunk + chunk) * CCH * ESZ;
-      auto one = [&](int q) {
-        const int tap = q / OB, b = q % OB;
-        const uint8_t* src = wld.p[0];
-#pragma unroll
-        for (int bb = 1; bb < OB; ++bb) src = (b == bb) ? wld.p[bb] : src;
-        lds_dma16(src + int64_t(tap) * a.Cpad * ESZ + coff, wl_addr + slot * wbytes + q * 1024);
-      };
       if constexpr (KH > 0) {
 #pragma unroll
         for (int k = 0; k < NWI; ++k) {
-          const int q = pwave + 4 * k;
-          one(q < n_wq ? q : n_wq - 1);
+          const int tap = k / OB, b = k % OB;
+          int o = o0_ + b * 32 + wrow;
+          o = o < a.O ? o : a.O - 1;                      // rows past O are never stored
+          w.off[k] = uint32_t(o * wr_row + wcol + int64_t(tap) * a.Cpad * ESZ);
         }
       } else {
-        for (int q = pwave; q < n_wq; q += 4) one(q);
+#pragma unroll
+        for (int b = 0; b < OB; ++b) {
+          int o = o0_ + b * 32 + wrow;
+          o = o < a.O ? o : a.O - 1;
+          w.off[b] = uint32_t(o * wr_row + wcol);
+        }
+      }
+    };
+    WSrc wld;
+    const uint32_t wl_addr = lds_addr_of(wl);
+    // `wbase` = wr + byte offset of the chunk within a weight row (scalar).
+    auto issue_weights = [&](const uint8_t* wbase, int slot) {
+      if constexpr (KH > 0) {
+#pragma unroll
+        for (int k = 0; k < NWI; ++k) lds_dma16_off(wbase, wld.off[k], wl_addr + slot * wbytes + k * 1024);
+      } else {
+        for (int q = 0; q < n_wq; ++q) {
+          const int tap = q / OB, b = q % OB;
+          uint32_t off = wld.off[0];
+#pragma unroll
+          for (int bb = 1; bb < OB; ++bb) off = (b == bb) ? wld.off[bb] : off;
+          lds_dma16_off(wbase + int64_t(tap) * a.Cpad * ESZ, off, wl_addr + slot * wbytes + q * 1024);
+        }
       }
     };
 
     RingReg<LB> preg[D][MAXI][G];
-    Items ld, st;             // items of the tile being loaded and of the tile being stored
-    auto chunk_base = [&](int item) { return (lg(item) & (ksplit - 1)) * nchunk; };
-    auto load_patch = [&](int item, int chunk, auto slot_) {
+    Loads ld;                 // items of the tile being loaded
+    Stores st_next, st;       // of the tile being loaded and of the tile being stored
+    auto split_of = [&](int item) { return lg(item) & (ksplit - 1); };
+    // `abase` = act + byte offset of the chunk's first channel plane (scalar).
+    auto load_patch = [&](const uint8_t* abase, auto slot_) {
       constexpr int slot = decltype(slot_)::value;
-      const int64_t coff = int64_t(chunk_base(item) + chunk) * CCH * plane;
 #pragma unroll
       for (int i = 0; i < MAXI; ++i) {
 #pragma unroll
-        for (int t = 0; t < G; ++t) preg[slot][i][t].load(ld.src[i] + coff + t * plane);
+        for (int t = 0; t < G; ++t) preg[slot][i][t].load(abase + ld.off[i][t]);
       }
     };
     // Items that do not exist read valid dummy addresses and write into a 512-byte dummy area
     // at lds + 512, so that no branch separates a ring load from its use.
-    auto store_patch = [&](auto slot_, int buf) {
-      constexpr int slot = decltype(slot_)::value;
+    auto store_patch = [&](auto slot_, auto buf_) {
+      constexpr int slot = decltype(slot_)::value, buf = decltype(buf_)::value;
 #pragma unroll
       for (int i = 0; i < MAXI; ++i) {
-        const int boff_ = ((st.okbits >> i) & 1u) ? buf * pbytes : 0;
-        uint8_t* pb = lds + st.dst[i][0] + boff_;
+        uint8_t* pb = lds + st.dst[buf][i][0];
 #pragma unroll
         for (int p = 0; p < VW; ++p) {
           i32x4 v;   // pixel p: element t = channel t of the group; one byte permute per two sources
@@ -324,74 +381,121 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
               v[d] = int32_t(__builtin_amdgcn_perm(t23, t01, 0x05040100u));
             }
           }
-          if constexpr (FLAT) *reinterpret_cast<i32x4*>(lds + st.dst[i][p] + boff_) = v;
+          if constexpr (FLAT) *reinterpret_cast<i32x4*>(lds + st.dst[buf][i][p]) = v;
           else *reinterpret_cast<i32x4*>(pb + p * PIXB) = v;
         }
       }
     };
-    // Cursor steps.  Past the last tile a cursor keeps its descriptors: surplus loads and weight
-    // transfers re-read valid addresses and are never consumed; surplus stores are skipped.
+    // Cursors.  Past the last tile a cursor keeps its descriptors and restarts at chunk 0 of its
+    // last tile: surplus loads and weight transfers re-read valid addresses and are never
+    // consumed; surplus stores are skipped.
     const int step = int(gridDim.x);
-    auto next_unit = [&](Cursor& c) {
-      bool new_tile = false;
-      if (++c.chunk == nchunk) {
-        c.chunk = 0;
-        c.tile += step;
-        new_tile = c.tile < n_tiles;
-      }
-      return new_tile;
+    struct Cursor {
+      int tile, chunk;
+      const uint8_t* base;      // scalar: start of the current chunk in the tensor the cursor reads
     };
-    Cursor lc = {tile, 0}, sc = {tile, 0}, wc = {tile, 0};
+    auto act_base = [&](int item) { return act + int64_t(split_of(item)) * nchunk * chunk_bytes; };
+    auto w_base = [&](int item) { return wr + int64_t(split_of(item)) * nchunk * (CCH * ESZ); };
+    Cursor lc = {tile, 0, act_base(tile)}, wc = {tile, 0, w_base(tile)};
+    int w_o0;                 // channel tile the weight offsets were made for
+    {
+      int m0_, mend_;
+      tile_range(tile, &m0_, &mend_, &w_o0);
+    }
+    int sc_tile = tile, sc_chunk = 0;
+    auto next_load = [&]() {
+      lc.base += chunk_bytes;
+      if (++lc.chunk == nchunk) {
+        lc.chunk = 0;
+        if (lc.tile + step < n_tiles) {
+          lc.tile += step;
+          make_items(lc.tile, ld, st_next);
+        }
+        lc.base = act_base(lc.tile);
+      }
+    };
+    auto next_weights = [&]() {
+      wc.base += CCH * ESZ;
+      if (++wc.chunk == nchunk) {
+        wc.chunk = 0;
+        if (wc.tile + step < n_tiles) {
+          wc.tile += step;
+          int m0_, mend_, o0_;
+          tile_range(wc.tile, &m0_, &mend_, &o0_);
+          if (o0_ != w_o0) {                        // uniform; rare: an XCD's items share channel tiles
+            w_o0 = o0_;
+            make_wsrc(wc.tile, wld);
+          }
+        }
+        wc.base = w_base(wc.tile);
+      }
+    };
+    // The store cursor enters a tile D units after the load cursor did and, in program order,
+    // before the load cursor can leave it (chunks per item are a multiple of D): the load
+    // cursor's store descriptors are that tile's.
+    auto next_store = [&]() {
+      if (++sc_chunk == nchunk) {
+        sc_chunk = 0;
+        sc_tile += step;
+        st = st_next;
+      }
+    };
 
-    // ---- prologue: ring and weight pipeline primed, chunk 0 of the first tile in LDS ----------
-    make_items(tile, ld);
-    st = ld;
-    make_wsrc(tile, wld);
+    if (pwave == 0) {
+      // ---- weight wave: NWB - 1 units ahead of the consumers ---------------------------------
+      make_wsrc(tile, wld);
+      static_for<NWB - 1>([&](auto k_) {
+        issue_weights(wc.base, decltype(k_)::value);
+        next_weights();
+      });
+      wait_vmem<0>();
+      lds_barrier();                                     // B0
+      int wslot = 0;                                     // LDS weight buffer of the current chunk
+      // The next chunk's weights must have landed at the end of a period: with three buffers
+      // they were sent a whole period earlier (only this period's transfers may be outstanding),
+      // with two buffers in this period.
+      constexpr int kWaitWeights = (KH > 0 && NWB == 3) ? NWI : 0;
+      for (; tile < n_tiles; tile += step) {
+        for (int ch = 0; ch < nchunk; ++ch) {
+          const int slot2 = wslot + NWB - 1 >= NWB ? wslot - 1 : wslot + NWB - 1;
+          issue_weights(wc.base, slot2);
+          next_weights();
+          wslot = wslot + 1 >= NWB ? 0 : wslot + 1;
+          wait_vmem<kWaitWeights>();
+          lds_barrier();
+        }
+      }
+      wait_vmem<0>();
+      return;
+    }
+    // ---- patch waves: ring primed, chunk 0 of the first tile in LDS ---------------------------
+    make_items(tile, ld, st_next);
+    st = st_next;
     static_for<D>([&](auto d_) {
-      load_patch(lc.tile, lc.chunk, d_);
-      if (next_unit(lc)) make_items(lc.tile, ld);
+      load_patch(lc.base, d_);
+      next_load();
     });
-    static_for<NWB - 1>([&](auto k_) {
-      issue_weights(wc.tile, wc.chunk, decltype(k_)::value);
-      if (next_unit(wc)) make_wsrc(wc.tile, wld);
-    });
-    store_patch(std::integral_constant<int, 0>{}, 0);     // nothing to clear: the buffers are zero
-    if (next_unit(sc)) make_items(sc.tile, st);
-    load_patch(lc.tile, lc.chunk, std::integral_constant<int, 0>{});
-    if (next_unit(lc)) make_items(lc.tile, ld);
-    wait_vmem<0>();
+    store_patch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});   // nothing to clear: the buffers are zero
+    next_store();
+    load_patch(lc.base, std::integral_constant<int, 0>{});
+    next_load();
     lds_barrier();                                       // B0: chunk 0 of the first tile is ready
-    int wslot = 0;                                       // LDS weight buffer of the current chunk
-    constexpr int RL = MAXI * G;
-    // Vector-memory instructions issued after the weights of the next chunk: with three buffers
-    // those were sent a whole period earlier (ring load, weights, ring load follow them), with
-    // two buffers in this period (only the ring load follows).
-    constexpr int kWaitWeights = KH > 0 ? (NWB == 3 ? 2 * RL + NWI : RL) : 0;
+    static_assert(D % 2 == 0, "the patch buffer of a stored unit follows from its ring slot");
 
     for (; tile < n_tiles; tile += step) {
       for (int cb = 0; cb < nchunk; cb += D) {
         static_for<D>([&](auto d_) {
           constexpr int d = decltype(d_)::value;      // the consumers multiply chunk cb + d now
           constexpr int ns = (d + 1) % D;             // ring slot of the unit stored (and refilled)
-          // the unit after it: registers -> LDS
-          if (sc.tile < n_tiles) {
-            if (sc.chunk <= 1) zero_invalid_rows(sc.tile, sc.chunk);   // first use of this buffer by the tile
-            store_patch(std::integral_constant<int, ns>{}, sc.chunk & 1);
+          // the unit after it: registers -> LDS.  Its chunk number is cb + d + 1 (mod the chunks
+          // of an item, an even number), so its patch buffer is (d + 1) % 2.
+          if (sc_tile < n_tiles) {
+            if (sc_chunk <= 1) zero_invalid_rows(st, sc_chunk);   // first use of this buffer by the tile
+            store_patch(std::integral_constant<int, ns>{}, std::integral_constant<int, (d + 1) & 1>{});
           }
-          // The store cursor enters a tile D units after the load cursor did and, in program
-          // order, before the load cursor can leave it (chunks per item are a multiple of D):
-          // the load cursor's descriptors are that tile's.
-          if (next_unit(sc)) st = ld;
-          {
-            const int slot2 = wslot + NWB - 1 >= NWB ? wslot - 1 : wslot + NWB - 1;
-            issue_weights(wc.tile, wc.chunk, slot2);
-            if (next_unit(wc)) make_wsrc(wc.tile, wld);
-          }
-          wslot = wslot + 1 >= NWB ? 0 : wslot + 1;
-          load_patch(lc.tile, lc.chunk, std::integral_constant<int, ns>{});
-          if (next_unit(lc)) make_items(lc.tile, ld);
-          if constexpr (KH > 0) wait_vmem<kWaitWeights>();
-          else wait_vmem<0>();
+          next_store();
+          load_patch(lc.base, std::integral_constant<int, ns>{});
+          next_load();
           lds_barrier();
         });
       }

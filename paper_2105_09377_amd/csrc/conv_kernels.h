@@ -37,6 +37,7 @@ struct ConvGeom {
   int max_rows;     // most patch rows any tile needs
   int pair_ok;      // W even: pixel pairs may be loaded with one access
   int tps;          // producer/consumer kernel: positions a tile covers (<= its MFMA width TP)
+  int rb_shift;     // producer/consumer kernel: log2 of the patch rows per block of producer items
   FastDiv dHWo, dWo;  // division by Ho*Wo and by Wo
 };
 
