@@ -91,6 +91,9 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   }
   g.max_rows = conv_max_rows(a, g.M, g.HWo, g.tps);
   if (g.max_rows < 0) return hipErrorInvalidValue;
+  g.dTiles = FastDiv::make(uint32_t(ceil_div(g.M, g.tps)));
+  g.dW = FastDiv::make(uint32_t(a.W));
+  g.dXG = FastDiv::make(1);
   // Patch row pitch: g.PW pixels of 48 bytes with g.PW * 3 / 2 odd, so that consecutive patch rows
   // of one pixel column fall on different 16-byte bank groups (the producers' LDS stores).
   while ((g.PW * 3 / 2) % 2 == 0) g.PW += 2;
@@ -119,6 +122,7 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
 #define GS_TRY(VW_, MAXI_)                                                                   \
   if (a.W % VW_ == 0 && items(VW_) <= 192 * MAXI_) {                                        \
     g.rb_shift = pick_rb(VW_, MAXI_);                                                        \
+    g.dXG = FastDiv::make(uint32_t(a.W / VW_));                                              \
     return launch_conv4_cfg<TR, TO, TP, WO, WP, VW_, KH, KW, MAXI_>(a, g, lds_bytes, s);      \
   }
 #define GS_TRY_FLAT(VW_, MAXI_)                                                              \

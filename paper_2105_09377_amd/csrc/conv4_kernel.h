@@ -101,7 +101,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   // fastest so that workgroups launched together share a patch.
   const int ksplit = a.ksplit, kshift = ksplit == 4 ? 2 : ksplit == 2 ? 1 : 0;
   const int n_tiles = tiles_m * ((a.O + TO - 1) / TO) * ksplit;
-  const FastDiv dTiles = FastDiv::make(uint32_t(tiles_m));
+  const FastDiv dTiles = g.dTiles;
   const int Kh = KH ? KH : a.Kh, Kw = KW ? KW : a.Kw;
   const int T = Kh * Kw;
   const int nchunk = a.Cpad / CCH / ksplit;   // chunks per work item: a multiple of D (checked by the host)
@@ -158,11 +158,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     const int64_t plane = int64_t(a.H) * a.W * ESZ;     // bytes per channel plane
     const int64_t wr_row = int64_t(T) * a.Cpad * ESZ;   // bytes per output channel in wr
     const int XGn = a.W / VW;                           // pixel groups per row
-    const FastDiv dXG = FastDiv::make(uint32_t(XGn));
+    const FastDiv dXG = g.dXG;
     const int n_wq = T * OB;
     const int64_t chunk_bytes = int64_t(CCH) * plane;   // activations: one chunk further
     constexpr int ND = FLAT ? VW : 1;                   // LDS destinations kept per item
-    const FastDiv dW = FastDiv::make(uint32_t(a.W));
+    const FastDiv dW = g.dW;
     const int pl_off = int(pl - lds);
 
     // Patch items of a tile, per thread.  The tensors have fewer than 2^31 elements (host check),
@@ -556,6 +556,18 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     constexpr int ROWS_PER_IT = 64 / GR;
     constexpr int NIT = 32 / ROWS_PER_IT;            // write-back steps per 32-channel block
     uint8_t* stage = sl + wave * (32 * RS);
+    // Results of one 32x32 block (rows = positions, columns = channels: a lane holds, for channel
+    // lane % 32, four consecutive positions per group of four registers) go to the staging rows
+    // [channel][position] as 16-byte stores; rows are RS = 16 (mod 256) bytes apart, so the 16
+    // lanes of a store pass hit 16 different bank groups.
+    auto stage_block = [&](const typename TR::accv_t& c, int n) {
+      uint8_t* row = stage + (lane & 31) * RS + (n * 32 + 4 * (lane >> 5)) * 4;
+      static_for<4>([&](auto gi_) {
+        constexpr int gi = decltype(gi_)::value;
+        const auto q = __builtin_shufflevector(c, c, 4 * gi, 4 * gi + 1, 4 * gi + 2, 4 * gi + 3);
+        *reinterpret_cast<i32x4*>(row + gi * 32) = __builtin_bit_cast(i32x4, q);
+      });
+    };
     const int gq = lane % GR, rsub = lane / GR;
     const int mm = m0 + wp * wpv + gq * 4;
     const bool grp_ok = gq * 4 < wpv && mm < M;
@@ -617,7 +629,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           for (int m = 0; m < MI; ++m)
 #pragma unroll
             for (int n = 0; n < NJ; ++n)
-              acc[m][n] = TR::mfma(fr[slot][m], fr[slot][MI + n], acc[m][n]);
+              acc[m][n] = TR::mfma(fr[slot][MI + n], fr[slot][m], acc[m][n]);
         });
       } else {
         for (int kh = 0; kh < Kh; ++kh)
@@ -634,7 +646,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
 #pragma unroll
             for (int m = 0; m < MI; ++m)
 #pragma unroll
-              for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(af[m], bf[n], acc[m][n]);
+              for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(bf[n], af[m], acc[m][n]);
           }
       }
       wslot = wslot + 1 >= NWB ? 0 : wslot + 1;
@@ -654,11 +666,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           constexpr int m = decltype(m_)::value;
           static_for<NJ>([&](auto n_) {
             constexpr int n = decltype(n_)::value;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-              *reinterpret_cast<typename TR::acc_t*>(stage + r * RS + (n * 32 + (lane & 31)) * 4) = acc[m][n][v];
-            }
+            stage_block(acc[m][n], n);
           });
           i32x4 raw[NIT];
 #pragma unroll
@@ -723,17 +731,24 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
         else write_back(std::integral_constant<int, 1>{});
       }
     } else {
-      static_for<NJ>([&](auto n_) {
-        constexpr int n = decltype(n_)::value;
-        static_for<MI>([&](auto m_) {
-          constexpr int m = decltype(m_)::value;
+      // Planes whose size is not a multiple of four positions: the same staging, read back one
+      // value per lane (lane % 32 = position, two channel rows per read) and stored one by one.
+      static_for<MI>([&](auto m_) {
+        constexpr int m = decltype(m_)::value;
+        static_for<NJ>([&](auto n_) { stage_block(acc[m][decltype(n_)::value], decltype(n_)::value); });
+        static_for<NJ>([&](auto n_) {
+          constexpr int n = decltype(n_)::value;
+          typename TR::acc_t val[16];
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int o = o0 + wo * WOT + m * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          for (int rr = 0; rr < 16; ++rr)
+            val[rr] = *reinterpret_cast<const typename TR::acc_t*>(stage + (2 * rr + (lane >> 5)) * RS +
+                                                                   (n * 32 + (lane & 31)) * 4);
+#pragma unroll
+          for (int rr = 0; rr < 16; ++rr) {
+            const int o = o0 + wo * WOT + m * 32 + 2 * rr + (lane >> 5);
             if (pos_ok[n] && o < a.O)
               store_result<typename TR::acc_t>(outp, has_res ? a.residual : nullptr, odt,
-                                               out_base[n] + uint32_t(o) * uint32_t(g.HWo), acc[m][n][v],
-                                               relu);
+                                               out_base[n] + uint32_t(o) * uint32_t(g.HWo), val[rr], relu);
           }
         });
       });

@@ -39,6 +39,7 @@ struct ConvGeom {
   int tps;          // producer/consumer kernel: positions a tile covers (<= its MFMA width TP)
   int rb_shift;     // producer/consumer kernel: log2 of the patch rows per block of producer items
   FastDiv dHWo, dWo;  // division by Ho*Wo and by Wo
+  FastDiv dTiles, dXG, dW;   // producer/consumer kernel: by position tiles, pixel groups per row, W
 };
 
 struct SegTable {
