@@ -200,6 +200,64 @@ int glenside_pad(const gs_ap* in, int dim, int64_t lo, int64_t hi, int pad_mode,
 /* `pair` (Table 1; Sec. 5.4): two patterns of one shape ((a..),(c..)) -> ((a..),(2, c..)).        */
 int glenside_pair(const gs_ap* a, const gs_ap* b, gs_ap* out, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Programs as text.  The paper writes kernels as s-expressions over the transformers of Table 1
+ * and the operators of Table 2 (Figs. 2a-2c, 5, 7).  Text conventions: a symbol that names one of
+ * `tensors` is that tensor (all compute dimensions until `access`ed); any other symbol is looked
+ * up in `ints` (the C, Kh, Sh ... of the listings); (shape d0 d1 ...) and (list i0 i1 ...) are
+ * integer tuples; the shape literal of `reshape` is written as two tuples,
+ * (reshape X (shape c...) (shape d...)).  EXT: (pad X dim lo hi) pads with zeros, `relu` is an
+ * operator.  Transformers: access transpose cartProd windows slice squeeze flatten reshape pair
+ * concat; (compute dotProd|reduceSum|reduceMax X); (systolicArray rows cols a0 w) (Sec. 5.2).
+ * The name strings and the two arrays are HOST memory read during the call.                     */
+typedef struct {
+  const char* name;
+  gs_ap tensor;               /* device data, dtype, rank, shape; n_access is ignored           */
+} gs_named_ap;
+typedef struct {
+  const char* name;
+  int64_t value;
+} gs_named_int;
+
+/* Access-pattern shape, split and element type of the program's result (the shape rules of
+ * Table 1 / Table 2 applied bottom-up).  Fills everything in `out` but leaves out->data.  Host only.
+ * Contractions give GS_I32 (int8 operands) or GS_F32 (bfloat16 operands).                       */
+int glenside_program_shape(const char* text, const gs_named_ap* tensors, int n_tensors,
+                           const gs_named_int* ints, int n_ints, gs_ap* out);
+/* Evaluates the program on the GPU into `out` (shape and split as glenside_program_shape gives;
+ * dtype the same, or GS_BF16 where the root is a bfloat16 contraction).  Node by node:
+ *   (compute dotProd (cartProd a0 a1))   one MFMA contraction; the Cartesian product is never
+ *                                        formed (the pattern Fig. 3 maps to hardware);
+ *   the whole listing of Fig. 2a         the direct convolution (windows formed on chip);
+ *   (compute reduceX (windows ...))      the fused pooling kernel (Fig. 2c);
+ *   (compute reduceX (pair a b))         the element-wise kernel (Sec. 5.4);
+ *   access squeeze flatten reshape,
+ *   a slice of the outermost dimension   descriptor changes, no data moves;
+ *   transpose slice concat pair pad
+ *   windows                              the data-moving kernels, into the workspace;
+ *   cartProd anywhere else               GS_ERR_UNSUPPORTED.
+ * Identical sub-programs are evaluated once.  `workspace`: device memory of at least
+ * glenside_program_workspace bytes (0 = invalid program), 16-byte aligned, caller-owned.       */
+int glenside_program_eval(const char* text, const gs_named_ap* tensors, int n_tensors,
+                          const gs_named_int* ints, int n_ints, gs_ap* out, void* workspace,
+                          size_t workspace_bytes, void* stream);
+size_t glenside_program_workspace(const char* text, const gs_named_ap* tensors, int n_tensors,
+                                  const gs_named_int* ints, int n_ints);
+/* Applies rewrite rules of the paper to a program and writes the new program text (host only).
+ *   "im2col"   : the three rules of Fig. 4, in order, at the dotProd over cartProd: derives Fig. 5
+ *                from Fig. 2a;
+ *   "systolic" : the rule of Fig. 3;
+ *   "block"    : the rules of Fig. 6 with params = {block_m, block_n, block_k}: operands
+ *                ((M),(K)) and ((N),(K)) of the dotProd over cartProd are split by rule 1 and the
+ *                other rules push cartProd and dotProd through the concats: derives a program of
+ *                block products joined by concat and reduceSum (pair ...) (Fig. 7) from Fig. 2b.
+ * The result's shape is checked to equal the input's.  out_text: HOST buffer of out_capacity
+ * bytes; *out_needed (may be NULL) receives the bytes needed; GS_ERR_WORKSPACE if too small;
+ * GS_ERR_UNSUPPORTED if no rule of the strategy applies.                                        */
+int glenside_program_rewrite(const char* text, const char* strategy, const int64_t* params, int n_params,
+                             const gs_named_ap* tensors, int n_tensors, const gs_named_int* ints,
+                             int n_ints, char* out_text, size_t out_capacity, size_t* out_needed);
+
 #ifdef __cplusplus
 }
 #endif

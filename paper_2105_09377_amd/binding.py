@@ -35,6 +35,8 @@ EXPORTS = (
     "glenside_conv2d_direct_packed", "glenside_transpose", "glenside_slice", "glenside_concat",
     "glenside_pad", "glenside_pair", "glenside_cartesian_dot_blocked",
     "glenside_conv2d_direct_static", "glenside_conv2d_direct_static_limit",
+    "glenside_program_shape", "glenside_program_eval", "glenside_program_workspace",
+    "glenside_program_rewrite",
 )
 
 
@@ -42,6 +44,14 @@ class gs_ap(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("rank", ctypes.c_int32),
                 ("n_access", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("shape", ctypes.c_int64 * GS_MAX_RANK)]
+
+
+class gs_named_ap(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("tensor", gs_ap)]
+
+
+class gs_named_int(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("value", ctypes.c_int64)]
 
 
 class GlensideError(RuntimeError):
@@ -75,6 +85,15 @@ def lib() -> ctypes.CDLL:
         L.glenside_conv2d_direct_static.argtypes = [ap_p, ap_p, i64_p, i64_p, ap_p, ctypes.c_int, ap_p, vp]
         L.glenside_conv2d_direct_static_limit.restype = ctypes.c_size_t
         L.glenside_conv2d_direct_static_limit.argtypes = []
+        nap_p, nint_p = ctypes.POINTER(gs_named_ap), ctypes.POINTER(gs_named_int)
+        prog = [ctypes.c_char_p, nap_p, ctypes.c_int, nint_p, ctypes.c_int]
+        L.glenside_program_shape.argtypes = prog + [ap_p]
+        L.glenside_program_workspace.argtypes = prog
+        L.glenside_program_workspace.restype = ctypes.c_size_t
+        L.glenside_program_eval.argtypes = prog + [ap_p, vp, ctypes.c_size_t, vp]
+        L.glenside_program_rewrite.argtypes = [ctypes.c_char_p, ctypes.c_char_p, i64_p, ctypes.c_int, nap_p,
+                                               ctypes.c_int, nint_p, ctypes.c_int, ctypes.c_char_p,
+                                               ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
         L.glenside_conv2d_pack_weights.argtypes = [ap_p, vp, ctypes.c_size_t, vp]
         L.glenside_conv2d_direct_packed.argtypes = conv
         L.glenside_reduce.argtypes = [ap_p, ctypes.c_int, ctypes.c_float, ap_p, vp]
@@ -380,3 +399,77 @@ def cartesian_dot_blocked(a0: torch.Tensor, a1: torch.Tensor, tile_m: int, tile_
                                                 tile_m, tile_n, tile_k, ctypes.byref(make_ap(out, 2)),
                                                 _stream(a0)), "cartesian_dot_blocked")
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# programs as text
+# ---------------------------------------------------------------------------------------------
+
+_META_DTYPES = {v: k for k, v in _DTYPES.items()}
+
+
+def _named(tensors, ints):
+    """Marshal {name: tensor or (shape, dtype)} and {name: int}; returns the arrays and what keeps them alive."""
+    keep = []
+    ta = (gs_named_ap * max(len(tensors), 1))()
+    for i, (name, t) in enumerate(tensors.items()):
+        nb = name.encode()
+        keep.append(nb)
+        ta[i].name = nb
+        if isinstance(t, torch.Tensor):
+            ta[i].tensor = make_ap(t, 0)
+        else:                                   # shape and dtype only (host-side queries)
+            shape, dtype = t
+            ap = gs_ap()
+            ap.dtype, ap.rank = _DTYPES[dtype], len(shape)
+            for d, v in enumerate(shape):
+                ap.shape[d] = int(v)
+            ta[i].tensor = ap
+    ia = (gs_named_int * max(len(ints), 1))()
+    for i, (name, v) in enumerate(ints.items()):
+        nb = name.encode()
+        keep.append(nb)
+        ia[i].name = nb
+        ia[i].value = int(v)
+    return ta, len(tensors), ia, len(ints), keep
+
+
+def program_shape(text: str, tensors, ints=None):
+    """Shape rule of a whole program: returns (shape tuple, n_access, torch dtype)."""
+    ta, nt, ia, ni, _keep = _named(tensors, ints or {})
+    out = gs_ap()
+    _check(lib().glenside_program_shape(text.encode(), ta, nt, ia, ni, ctypes.byref(out)), "program_shape")
+    return tuple(out.shape[i] for i in range(out.rank)), out.n_access, _META_DTYPES[out.dtype]
+
+
+def program_eval(text: str, tensors, ints=None, out_dtype=None, out: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Evaluate an access-pattern program (the paper's s-expression text) on the GPU."""
+    ints = ints or {}
+    ta, nt, ia, ni, _keep = _named(tensors, ints)
+    L = lib()
+    shape, na, dtype = program_shape(text, tensors, ints)
+    first = next(iter(tensors.values()))
+    if out is None:
+        out = torch.empty(shape, dtype=out_dtype or dtype, device=first.device)
+    if workspace is None:
+        need = L.glenside_program_workspace(text.encode(), ta, nt, ia, ni)
+        workspace = torch.empty(max(int(need), 16), dtype=torch.uint8, device=first.device)
+    _check(L.glenside_program_eval(text.encode(), ta, nt, ia, ni, ctypes.byref(make_ap(out, na, shape=shape)),
+                                   workspace.data_ptr(), workspace.numel(), _stream(first)), "program_eval")
+    return out
+
+
+def program_rewrite(text: str, strategy: str, tensors, ints=None, params: Sequence[int] = ()) -> str:
+    """Apply the paper's rewrite rules ("im2col", "systolic", "block" with params (bm, bn, bk))."""
+    ta, nt, ia, ni, _keep = _named(tensors, ints or {})
+    L = lib()
+    need = ctypes.c_size_t(0)
+    st = L.glenside_program_rewrite(text.encode(), strategy.encode(), _i64(params) if params else None,
+                                    len(params), ta, nt, ia, ni, None, 0, ctypes.byref(need))
+    if st != GS_ERR_WORKSPACE:
+        _check(st, "program_rewrite")
+    buf = ctypes.create_string_buffer(need.value)
+    _check(L.glenside_program_rewrite(text.encode(), strategy.encode(), _i64(params) if params else None,
+                                      len(params), ta, nt, ia, ni, buf, need.value, None), "program_rewrite")
+    return buf.value.decode()
