@@ -29,6 +29,7 @@ import torch  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_I8_TOPS = 5000.0         # MI355X dense int8 MFMA
+PEAK_F8_TFLOPS = 5000.0       # MI355X dense fp8 MFMA
 PEAK_HBM_GBS = 8000.0
 ROTATE_BYTES = 512 << 20      # rotate over enough buffer sets to exceed the last-level cache
 DOM_BATCH = 20                # launches of the dominant kernel per timing graph
@@ -395,6 +396,64 @@ class DenseBig(_Simple):
                 "kind": "oracle", "sample": f"brute-force C loops (fp64, OpenMP) on a 256 x 512 block of the result, {dt:.2f} s"}
 
 
+class DenseInt8(DenseBig):
+    """The same product on int8 operands (the int8 datapath of the paper's accelerators), int32 result."""
+
+    name = "cartesian_dot ((8192),(8192)) x ((8192),(8192)) int8 -> int32"
+    dtype = "i8"
+    bound, unit, peak = "mfma", "TOP/s", PEAK_I8_TOPS
+
+    def __init__(self, dev):
+        from paper_2105_09377_amd import binding as gs, synth
+        self.gs = gs
+        self.a = synth.uniform_int8((8192, 8192), -127, 127, 7311)
+        self.b = synth.uniform_int8((8192, 8192), -127, 127, 7312)
+        self.work = 2.0 * 8192 ** 3
+        self.nsets = 2
+        self.as_ = [self.a.to(dev).clone() for _ in range(self.nsets)]
+        self.bs = [self.b.to(dev).clone() for _ in range(self.nsets)]
+        self.outs = [torch.empty((8192, 8192), dtype=torch.int32, device=dev) for _ in range(self.nsets)]
+
+    def cpu_baseline(self):
+        from oracle import brute
+        a, b = self.a[:256].numpy().astype("int64"), self.b[:512].numpy().astype("int64")
+        t0 = time.perf_counter()
+        brute.matmul(a, b.T)
+        dt = time.perf_counter() - t0
+        return {"value": 2.0 * 256 * 512 * 8192 / dt / 1e12, "unit": "TOP/s", "cores": brute.num_threads(),
+                "kind": "oracle", "sample": f"brute-force C loops (int64, OpenMP) on a 256 x 512 block of the result, {dt:.2f} s"}
+
+
+class DenseFp8(DenseBig):
+    """The same product on 8-bit float operands (OCP e4m3), fp32 accumulate, bf16 result."""
+
+    name = "cartesian_dot ((8192),(8192)) x ((8192),(8192)) fp8 e4m3 -> bf16"
+    dtype = "f8"
+    bound, unit, peak = "mfma", "TFLOP/s", PEAK_F8_TFLOPS
+
+    def __init__(self, dev):
+        from paper_2105_09377_amd import binding as gs, synth
+        self.gs = gs
+        self.a = synth.normal_fp8((8192, 8192), 1.0, 7321)
+        self.b = synth.normal_fp8((8192, 8192), 8192 ** -0.5, 7322)
+        self.work = 2.0 * 8192 ** 3
+        self.nsets = 2
+        self.as_ = [self.a.to(dev).clone() for _ in range(self.nsets)]
+        self.bs = [self.b.to(dev).clone() for _ in range(self.nsets)]
+        self.outs = [torch.empty((8192, 8192), dtype=torch.bfloat16, device=dev) for _ in range(self.nsets)]
+
+    def cpu_baseline(self):
+        import numpy as np
+        from oracle import brute, numerics
+        a = numerics.e4m3_bits_to_f64(self.a[:256].view(torch.uint8).numpy())
+        b = numerics.e4m3_bits_to_f64(self.b[:512].view(torch.uint8).numpy())
+        t0 = time.perf_counter()
+        brute.matmul(a, np.ascontiguousarray(b.T))
+        dt = time.perf_counter() - t0
+        return {"value": 2.0 * 256 * 512 * 8192 / dt / 1e12, "unit": "TFLOP/s", "cores": brute.num_threads(),
+                "kind": "oracle", "sample": f"brute-force C loops (fp64, OpenMP) on a 256 x 512 block of the result, {dt:.2f} s"}
+
+
 class DenseBlocked(_Simple):
     """The blocked form of the product (slice / dotProd / pair + reduceSum / concat, one launch per
     block and K slice) on 2048 x 2048 x 2048 bf16 with cubic blocks of TILE: the tile-shape sweep
@@ -487,7 +546,7 @@ class MlpScaled(Mlp):
 
 
 WORKLOADS = {"conv3x3": Conv3x3, "conv3x3_b64": Conv3x3Batch64, "conv3x3_i8": Conv3x3Int8, "resnet18": ResNet18, "im2col_gather": Im2colGather, "maxpool": MaxPool,
-             "reduce": RowReduce, "transpose": Transpose, "dense": DenseBig, "dense_blocked": DenseBlocked, "mlp": Mlp, "mlp_scaled": MlpScaled}
+             "reduce": RowReduce, "transpose": Transpose, "dense": DenseBig, "dense_i8": DenseInt8, "dense_fp8": DenseFp8, "dense_blocked": DenseBlocked, "mlp": Mlp, "mlp_scaled": MlpScaled}
 
 
 def main():

@@ -46,7 +46,9 @@ typedef enum {
   GS_ERR_LAUNCH = 7       /* HIP reported an error when launching                         */
 } gs_status;
 
-typedef enum { GS_I8 = 0, GS_I32 = 1, GS_BF16 = 2, GS_F32 = 3 } gs_dtype;
+/* GS_F8 (EXT): 8-bit float, OCP e4m3 (1-4-3, bias 7, no infinities, maximum 448); accepted as the
+ * operand type of glenside_cartesian_dot (and of dotProd in programs) only.                       */
+typedef enum { GS_I8 = 0, GS_I32 = 1, GS_BF16 = 2, GS_F32 = 3, GS_F8 = 4 } gs_dtype;
 typedef enum { GS_SUM = 0, GS_MAX = 1 } gs_reduce_op;
 typedef enum { GS_ACT_NONE = 0, GS_ACT_RELU = 1 } gs_activation;
 /* EXT: what a padded cell reads: zero (for dotProd / reduceSum consumers) or the lowest value of
@@ -84,8 +86,9 @@ int glenside_access_windows(const gs_ap* in, const int64_t* window, const int64_
 /* `compute dotProd (cartProd a0 a1)` -- Fig. 2b and the left-hand side of the systolic-array
  * rewrite (Sec. 5.2).  a0 ((m..),(k..)), a1 ((n..),(k..)) with equal compute shapes ->
  * out ((m.., n..),()):  out[m, n] = sum_k a0[m, k] * a1[n, k].
- * Types: i8 x i8 -> i32;  bf16 x bf16 -> f32 or bf16 (fp32 accumulate).  EXT: act applies ReLU
- * to the result.  workspace is unused at present (pass NULL, 0).                                */
+ * Types: i8 x i8 -> i32;  bf16 x bf16 -> f32 or bf16 (fp32 accumulate);  EXT f8 x f8 -> f32 or
+ * bf16 (fp32 accumulate).  EXT: act applies ReLU to the result.  workspace is unused (pass NULL,
+ * 0): no shape of this contraction splits its sum across workgroups.                            */
 int glenside_cartesian_dot(const gs_ap* a0, const gs_ap* a1, gs_ap* out, int act,
                            void* workspace, size_t workspace_bytes, void* stream);
 

@@ -18,14 +18,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libglenside.so")
 
 GS_MAX_RANK = 8
-GS_I8, GS_I32, GS_BF16, GS_F32 = 0, 1, 2, 3
+GS_I8, GS_I32, GS_BF16, GS_F32, GS_F8 = 0, 1, 2, 3, 4
 GS_SUM, GS_MAX = 0, 1
 GS_ACT_NONE, GS_ACT_RELU = 0, 1
 GS_PAD_ZERO, GS_PAD_LOWEST = 0, 1
 (GS_OK, GS_ERR_NULL, GS_ERR_RANK, GS_ERR_SHAPE, GS_ERR_DTYPE, GS_ERR_UNSUPPORTED,
  GS_ERR_WORKSPACE, GS_ERR_LAUNCH) = range(8)
 
-_DTYPES = {torch.int8: GS_I8, torch.int32: GS_I32, torch.bfloat16: GS_BF16, torch.float32: GS_F32}
+_DTYPES = {torch.int8: GS_I8, torch.int32: GS_I32, torch.bfloat16: GS_BF16, torch.float32: GS_F32,
+           torch.float8_e4m3fn: GS_F8}
 
 EXPORTS = (
     "glenside_status_string", "glenside_windows_out_shape", "glenside_access_windows",

@@ -27,7 +27,7 @@ int check_ap(const gs_ap* a, bool need_data) {
   if (!a) return GS_ERR_NULL;
   if (a->rank < 0 || a->rank > GS_MAX_RANK) return GS_ERR_RANK;
   if (a->n_access < 0 || a->n_access > a->rank) return GS_ERR_RANK;
-  if (a->dtype < GS_I8 || a->dtype > GS_F32) return GS_ERR_DTYPE;
+  if (a->dtype < GS_I8 || a->dtype > GS_F8) return GS_ERR_DTYPE;
   if (a->reserved != 0) return GS_ERR_UNSUPPORTED;
   int64_t n = 1;
   for (int i = 0; i < a->rank; ++i) {
@@ -54,6 +54,7 @@ uint32_t lowest_bits(int dtype) {
     case GS_I8: return 0x80u;
     case GS_I32: return 0x80000000u;
     case GS_BF16: return 0xff80u;       // -inf
+    case GS_F8: return 0xfeu;           // -448: e4m3 has no infinity
     default: return 0xff800000u;        // -inf
   }
 }
@@ -235,7 +236,7 @@ int glenside_cartesian_dot(const gs_ap* a0, const gs_ap* a1, gs_ap* out, int act
   if (a0->dtype != a1->dtype) return GS_ERR_DTYPE;
   if (a0->dtype == GS_I8) {
     if (out->dtype != GS_I32) return GS_ERR_DTYPE;
-  } else if (a0->dtype == GS_BF16) {
+  } else if (a0->dtype == GS_BF16 || a0->dtype == GS_F8) {
     if (out->dtype != GS_F32 && out->dtype != GS_BF16) return GS_ERR_DTYPE;
   } else {
     return GS_ERR_DTYPE;
@@ -274,7 +275,7 @@ int glenside_cartesian_dot_blocked(const gs_ap* a0, const gs_ap* a1, int64_t til
   // Partial sums of the K blocks are folded in the result, which therefore has the accumulator's type.
   if (a0->dtype == GS_I8) {
     if (out->dtype != GS_I32) return GS_ERR_DTYPE;
-  } else if (a0->dtype == GS_BF16) {
+  } else if (a0->dtype == GS_BF16 || a0->dtype == GS_F8) {
     if (out->dtype != GS_F32) return GS_ERR_DTYPE;
   } else {
     return GS_ERR_DTYPE;
@@ -541,8 +542,10 @@ int glenside_reduce(const gs_ap* in, int op, float scale, gs_ap* out, void* stre
     if (out->dtype != GS_I32) return GS_ERR_DTYPE;
   } else if (in->dtype == GS_BF16) {
     if (out->dtype != GS_BF16 && out->dtype != GS_F32) return GS_ERR_DTYPE;
-  } else {
+  } else if (in->dtype == GS_F32) {
     if (out->dtype != GS_F32) return GS_ERR_DTYPE;
+  } else {
+    return GS_ERR_DTYPE;                 // 8-bit floats are contraction operands only
   }
   if ((is_int || op == GS_MAX) && scale != 1.0f) return GS_ERR_UNSUPPORTED;
   const int64_t cols = compute_numel(in);
@@ -584,8 +587,10 @@ int glenside_windows_reduce(const gs_ap* in, const int64_t* window, const int64_
     if (out->dtype != GS_I32) return GS_ERR_DTYPE;
   } else if (in->dtype == GS_BF16) {
     if (out->dtype != GS_BF16 && out->dtype != GS_F32) return GS_ERR_DTYPE;
-  } else {
+  } else if (in->dtype == GS_F32) {
     if (out->dtype != GS_F32) return GS_ERR_DTYPE;
+  } else {
+    return GS_ERR_DTYPE;                 // 8-bit floats are contraction operands only
   }
   if ((is_int || op == GS_MAX) && scale != 1.0f) return GS_ERR_UNSUPPORTED;
   WindowsReduceArgs a;
@@ -625,7 +630,8 @@ int glenside_pair_reduce(const gs_ap* a, const gs_ap* b, int op, int act, gs_ap*
   if (!same_shape(a, b)) return GS_ERR_SHAPE;
   if (out->rank != a->rank) return GS_ERR_RANK;
   if (!same_shape(a, out)) return GS_ERR_SHAPE;
-  if (a->dtype != b->dtype || a->dtype != out->dtype || a->dtype == GS_I8) return GS_ERR_DTYPE;
+  if (a->dtype != b->dtype || a->dtype != out->dtype || a->dtype == GS_I8 || a->dtype == GS_F8)
+    return GS_ERR_DTYPE;
   PairArgs p;
   memset(&p, 0, sizeof(p));
   p.a = a->data;

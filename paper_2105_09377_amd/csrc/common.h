@@ -123,7 +123,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 __host__ __device__ inline size_t dtype_size(int dt) {
-  return dt == GS_I8 ? 1 : dt == GS_BF16 ? 2 : 4;
+  return (dt == GS_I8 || dt == GS_F8) ? 1 : dt == GS_BF16 ? 2 : 4;
 }
 
 // bfloat16 is the upper half of an IEEE binary32.
@@ -145,6 +145,7 @@ struct Bf16Traits {
   using acc_t = float;
   using accv_t = f32x16;
   static constexpr int kEsz = 2;
+  static constexpr int kStep = 32;      // bytes of K per row that one MFMA consumes
   __device__ static inline accv_t mfma(const i32x4& a, const i32x4& b, const accv_t& c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -155,10 +156,35 @@ struct I8Traits {
   using acc_t = int32_t;
   using accv_t = i32x16;
   static constexpr int kEsz = 1;
+  static constexpr int kStep = 32;
   __device__ static inline accv_t mfma(const i32x4& a, const i32x4& b, const accv_t& c) {
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
   }
 };
+
+// EXT: 8-bit floats (OCP e4m3).  One MFMA consumes 64 bytes of K per row: lanes 0-31 supply bytes
+// [0,32), lanes 32-63 bytes [32,64) of the K step, as two 16-byte pieces each; both operands are
+// cut the same way, so every byte of a row meets the byte of the same K index.  Unscaled (the
+// block scales of the instruction are left at one).
+typedef int32_t i32x8 __attribute__((ext_vector_type(8)));
+struct Fp8Traits {
+  using acc_t = float;
+  using accv_t = f32x16;
+  static constexpr int kEsz = 1;
+  static constexpr int kStep = 64;
+  __device__ static inline accv_t mfma(const i32x4* a, const i32x4* b, const accv_t& c) {
+    const i32x8 x = {a[0][0], a[0][1], a[0][2], a[0][3], a[1][0], a[1][1], a[1][2], a[1][3]};
+    const i32x8 y = {b[0][0], b[0][1], b[0][2], b[0][3], b[1][0], b[1][1], b[1][2], b[1][3]};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(x, y, c, 0, 0, 0, 0, 0, 0);
+  }
+};
+// Fragments are arrays of 16-byte pieces: one piece for 32-byte K steps, two for 64-byte ones.
+template <typename TR>
+__device__ __forceinline__ typename TR::accv_t mfma_pieces(const i32x4* a, const i32x4* b,
+                                                          const typename TR::accv_t& c) {
+  if constexpr (TR::kStep == 32) return TR::mfma(a[0], b[0], c);
+  else return TR::mfma(a, b, c);
+}
 
 // Epilogue shared by the contractions: optional residual, optional ReLU, store in the output
 // type.  `addr` is an element offset.
@@ -226,7 +252,7 @@ struct GemmArgs {         // C[i][j] = sum_k X[i][k] * Y[j][k]
   const void* y;          // J x K, row stride ldy elements
   void* out;
   const void* residual;   // same addressing as out, may be null
-  int in_dtype;           // GS_I8 or GS_BF16
+  int in_dtype;           // GS_I8, GS_BF16 or GS_F8
   int out_dtype;
   int64_t I, J, K, ldx, ldy;
   int64_t jp;             // out element offset = (j / jp) * (I * jp) + i * jp + (j % jp)

@@ -128,15 +128,22 @@ __global__ void __launch_bounds__(256) gemm_nt_checked_kernel(GemmArgs a) {
   load_slab(0);
   store_slab(0);
   __syncthreads();
-  const int frag_off = (lane & 31) * kRowBytes + (lane >> 5) * 16;
+  constexpr int KST = TR::kStep, P = KST / 32;    // bytes of K per MFMA step; 16-byte pieces per lane
+  const int frag_off = (lane & 31) * kRowBytes + (lane >> 5) * (KST / 2);
   for (int slab = 0; slab < nslab; ++slab) {
     if (slab + 1 < nslab) load_slab(slab + 1);
     const uint8_t* xs = lds + (slab & 1) * kBuf + wm * 32 * kRowBytes + frag_off;
     const uint8_t* ys = lds + (slab & 1) * kBuf + kXBytes + wn * 32 * kRowBytes + frag_off;
 #pragma unroll
-    for (int ks = 0; ks < kSlabBytes / 32; ++ks)
-      acc = TR::mfma(*reinterpret_cast<const i32x4*>(xs + ks * 32),
-                     *reinterpret_cast<const i32x4*>(ys + ks * 32), acc);
+    for (int ks = 0; ks < kSlabBytes / KST; ++ks) {
+      i32x4 xf[P], yf[P];
+#pragma unroll
+      for (int f = 0; f < P; ++f) {
+        xf[f] = *reinterpret_cast<const i32x4*>(xs + ks * KST + f * 16);
+        yf[f] = *reinterpret_cast<const i32x4*>(ys + ks * KST + f * 16);
+      }
+      acc = mfma_pieces<TR>(xf, yf, acc);
+    }
     if (slab + 1 < nslab) store_slab((slab + 1) & 1);
     __syncthreads();
   }
@@ -174,7 +181,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   constexpr int XQ = BM / RPI / NW, YQ = BN / RPI / NW, Q = XQ + YQ;   // transfer instructions per wave and slab
   static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile rows must split over the waves");
   constexpr int kXBytes = BM * SB, kYBytes = BN * SB;
-  constexpr int KS = SB / 32;                     // MFMA K steps per slab
+  constexpr int KST = TR::kStep;                  // bytes of K per row and MFMA
+  constexpr int P = KST / 32;                     // 16-byte pieces a lane holds per operand block
+  constexpr int KS = SB / KST;                    // MFMA K steps per slab
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -186,10 +195,10 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   const uint8_t* X = static_cast<const uint8_t*>(a.x);
   const uint8_t* Y = static_cast<const uint8_t*>(a.y);
   const int64_t ldxb = a.ldx * TR::kEsz, ldyb = a.ldy * TR::kEsz;
-  // K is a whole number of 32-byte MFMA steps; the last slab may hold fewer than KS of them.
+  // K is a whole number of MFMA steps; the last slab may hold fewer than KS of them.
   const int64_t Kb = a.K * TR::kEsz;
   const int nslab = int(ceil_div(Kb, SB));
-  const int tail_steps = int((Kb - int64_t(nslab - 1) * SB) / 32);   // 1..KS steps in the last slab
+  const int tail_steps = int((Kb - int64_t(nslab - 1) * SB) / KST);   // 1..KS steps in the last slab
 
   // LDS slab layout: row r at r * SB bytes, its 16-byte column c at position c ^ swizzle(r) with
   // swizzle(r) = (r / RPB) % C.  The LDS has 64 four-byte banks and serves a 16-byte read 16 lanes
@@ -221,7 +230,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   }
   // In a short last slab the 16-byte columns past K are not multiplied; their lanes re-read
   // column 0 of the slab instead of running past the end of the row (and of the matrix).
-  const uint32_t tail_fix = (lcol >= tail_steps * 32) ? uint32_t(lcol) : 0u;
+  const uint32_t tail_fix = (lcol >= tail_steps * KST) ? uint32_t(lcol) : 0u;
   // LDS: [X buffers 0 .. NS-1 | Y buffers 0 .. NS-1].
   constexpr int kYBase = NS * kXBytes;
   static_assert((MI - 1) * 32 * SB < 65536 && (NJ - 1) * 32 * SB < 65536, "blocks by immediate offset");
@@ -247,16 +256,19 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   });
 
   // Fragment addresses in the buffer being multiplied: row (lane % 32) of a 32-row block, 16-byte
-  // column 2*ks + lane/32, swizzled; one address register per operand and K step, moved to the
-  // next buffer once per slab; the 32-row blocks of a wave by immediate offset.
-  const uint8_t* xa[KS];
-  const uint8_t* ya[KS];
+  // columns P*(2*ks + lane/32) + f for the pieces f < P, swizzled; one address register per
+  // operand, K step and piece, moved to the next buffer once per slab; the 32-row blocks of a wave
+  // by immediate offset.
+  const uint8_t* xa[KS * P];
+  const uint8_t* ya[KS * P];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    const int koff = ((2 * ks + (lane >> 5)) ^ (((lane & 31) / RPB) % C)) << 4;
-    xa[ks] = lds + (wm * WM + (lane & 31)) * SB + koff;
-    ya[ks] = lds + kYBase + (wn * WN + (lane & 31)) * SB + koff;
-  }
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int f = 0; f < P; ++f) {
+      const int koff = ((P * (2 * ks + (lane >> 5)) + f) ^ (((lane & 31) / RPB) % C)) << 4;
+      xa[ks * P + f] = lds + (wm * WM + (lane & 31)) * SB + koff;
+      ya[ks * P + f] = lds + kYBase + (wn * WN + (lane & 31)) * SB + koff;
+    }
   // The K loop is software-pipelined by hand.  Slabs s+1 .. s+NS-1 are in flight (or landed)
   // while slab s is multiplied.  The fragments of K step k + 1 are requested before the MFMAs of
   // step k are issued (two register sets; scheduling barriers keep the compiler from undoing that
@@ -271,13 +283,19 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   // back edge, under register pressure) would run before the data has arrived.  The loop bodies
   // are free of branches (steady state and drain are separate loops) so that the accumulators
   // stay in place.
-  i32x4 fr[2][MI + NJ];
+  i32x4 fr[2][(MI + NJ) * P];
   auto request = [&](auto ks_, auto slot_) {
     constexpr int ks = decltype(ks_)::value, slot = decltype(slot_)::value;
 #pragma unroll
-    for (int m = 0; m < MI; ++m) fr[slot][m] = *reinterpret_cast<const i32x4*>(xa[ks] + m * 32 * SB);
+    for (int m = 0; m < MI; ++m)
 #pragma unroll
-    for (int n = 0; n < NJ; ++n) fr[slot][MI + n] = *reinterpret_cast<const i32x4*>(ya[ks] + n * 32 * SB);
+      for (int f = 0; f < P; ++f)
+        fr[slot][m * P + f] = *reinterpret_cast<const i32x4*>(xa[ks * P + f] + m * 32 * SB);
+#pragma unroll
+    for (int n = 0; n < NJ; ++n)
+#pragma unroll
+      for (int f = 0; f < P; ++f)
+        fr[slot][(MI + n) * P + f] = *reinterpret_cast<const i32x4*>(ya[ks * P + f] + n * 32 * SB);
     __builtin_amdgcn_sched_barrier(0);
   };
   auto multiply = [&](auto slot_) {
@@ -285,7 +303,8 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
 #pragma unroll
     for (int m = 0; m < MI; ++m)
 #pragma unroll
-      for (int n = 0; n < NJ; ++n) acc[m][n] = TR::mfma(fr[slot][m], fr[slot][MI + n], acc[m][n]);
+      for (int n = 0; n < NJ; ++n)
+        acc[m][n] = mfma_pieces<TR>(&fr[slot][m * P], &fr[slot][(MI + n) * P], acc[m][n]);
     __builtin_amdgcn_sched_barrier(0);
   };
   using I0 = std::integral_constant<int, 0>;
@@ -310,7 +329,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
         buf = wrap ? 0 : buf + 1;
         const int dx = wrap ? -(NS - 1) * kXBytes : kXBytes, dy = wrap ? -(NS - 1) * kYBytes : kYBytes;
 #pragma unroll
-        for (int k = 0; k < KS; ++k) {
+        for (int k = 0; k < KS * P; ++k) {
           xa[k] += dx;
           ya[k] += dy;
         }
@@ -320,7 +339,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
           constexpr int i = decltype(i_)::value;
           if constexpr (i < MI * NJ) {
             constexpr int m = i / NJ, n = i % NJ;
-            acc[m][n] = TR::mfma(fr[slot][m], fr[slot][MI + n], acc[m][n]);
+            acc[m][n] = mfma_pieces<TR>(&fr[slot][m * P], &fr[slot][(MI + n) * P], acc[m][n]);
           }
           if constexpr (ISSUE && i < Q) issue_one(s + NS, done_buf, i_);
           __builtin_amdgcn_sched_barrier(0);
@@ -537,7 +556,7 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
                    reinterpret_cast<uintptr_t>(a.x) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.y) % 16 == 0;
   // whole MFMA steps, and 256 rows of either operand within reach of a 32-bit byte offset
-  const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % 32 == 0 && a.ldx * TR::kEsz < (int64_t(1) << 23) &&
+  const bool dma = vec && a.K > 0 && (a.K * TR::kEsz) % TR::kStep == 0 && a.ldx * TR::kEsz < (int64_t(1) << 23) &&
                    a.ldy * TR::kEsz < (int64_t(1) << 23);
   if (dma) {
     // Columns per lane of the vector write-back: groups of vj columns must not straddle a jp
@@ -564,7 +583,9 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.I == 0 || a.J == 0) return hipSuccess;
   if (ceil_div(a.I, 64) * ceil_div(a.J, 64) > 0x7fffffff) return hipErrorInvalidValue;
-  return a.in_dtype == GS_I8 ? launch_t<I8Traits>(a, s) : launch_t<Bf16Traits>(a, s);
+  if (a.in_dtype == GS_I8) return launch_t<I8Traits>(a, s);
+  if (a.in_dtype == GS_F8) return launch_t<Fp8Traits>(a, s);
+  return launch_t<Bf16Traits>(a, s);
 }
 
 }  // namespace gs

@@ -206,7 +206,7 @@ struct Shape {           // an access pattern's shape and element type
   int64_t compute_numel() const { return numel() / (access_numel() ? access_numel() : 1); }
 };
 
-int dot_out_dtype(int in) { return in == GS_I8 ? GS_I32 : in == GS_BF16 ? GS_F32 : -1; }
+int dot_out_dtype(int in) { return in == GS_I8 ? GS_I32 : (in == GS_BF16 || in == GS_F8) ? GS_F32 : -1; }
 
 // Shape of a node; GS_OK or the status that evaluation would return.
 int infer(const TreeP& t, const Env& env, Shape* out);
@@ -251,7 +251,7 @@ int infer(const TreeP& t, const Env& env, Shape* out) {
   if (t->kind == Tree::kSymbol) {
     const gs_ap* a = env.tensor(t->sym);
     if (!a) return GS_ERR_NULL;
-    if (a->rank < 0 || a->rank > GS_MAX_RANK || a->dtype < GS_I8 || a->dtype > GS_F32) return GS_ERR_RANK;
+    if (a->rank < 0 || a->rank > GS_MAX_RANK || a->dtype < GS_I8 || a->dtype > GS_F8) return GS_ERR_RANK;
     out->d.assign(a->shape, a->shape + a->rank);
     for (int64_t x : out->d)
       if (x < 0) return GS_ERR_SHAPE;

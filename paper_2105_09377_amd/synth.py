@@ -32,6 +32,13 @@ def normal_bf16(shape: Sequence[int], scale: float, stream: int) -> torch.Tensor
     return torch.from_numpy(x).to(torch.bfloat16)
 
 
+def normal_fp8(shape: Sequence[int], scale: float, stream: int) -> torch.Tensor:
+    """N(0,1) * scale, stored as a CPU float8_e4m3fn tensor (torch's round-to-nearest-even cast;
+    values beyond +-448 would become NaN in that cast, so they are clipped first)."""
+    x = _rng(stream).standard_normal(tuple(shape), dtype=np.float32) * np.float32(scale)
+    return torch.from_numpy(np.clip(x, -448.0, 448.0)).to(torch.float8_e4m3fn)
+
+
 def uniform_int8(shape: Sequence[int], lo: int, hi: int, stream: int) -> torch.Tensor:
     """Integers uniform in [lo, hi] inclusive, stored as a CPU int8 tensor."""
     x = _rng(stream).integers(lo, hi + 1, size=tuple(shape), dtype=np.int64)

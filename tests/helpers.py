@@ -12,6 +12,8 @@ def to_oracle(t: torch.Tensor) -> np.ndarray:
     if t.dtype == torch.bfloat16:
         bits = t.view(torch.int16).numpy().view(np.uint16)
         return numerics.bf16_bits_to_f64(bits)
+    if t.dtype == torch.float8_e4m3fn:
+        return numerics.e4m3_bits_to_f64(t.view(torch.uint8).numpy())
     if t.dtype in (torch.int8, torch.int32, torch.int64):
         return t.numpy().astype(np.int64)
     return t.numpy().astype(np.float64)

@@ -27,6 +27,8 @@ def gen(dtype, shape, stream, scale=1.0):
         return synth.uniform_int32(shape, -100000, 100000, stream)
     if dtype == "bf16":
         return synth.normal_bf16(shape, scale, stream)
+    if dtype == "fp8":
+        return synth.normal_fp8(shape, scale, stream)
     return synth.normal_f32(shape, scale, stream)
 
 
@@ -111,6 +113,14 @@ DOT_CASES = [
     ("i8", (64, 128), 1, (72, 128), 1, torch.int32, True),
     ("bf16", (40, 64), 1, (76, 64), 1, torch.bfloat16, False),
     ("bf16", (200, 256), 1, (264, 256), 1, torch.float32, False),
+    # 8-bit floats: 64-byte K steps; K not a multiple of 64 takes the checked kernel
+    ("fp8", (300, 328), 1, (200, 328), 1, torch.float32, False),
+    ("fp8", (130, 1000), 1, (70, 1000), 1, torch.bfloat16, True),
+    ("fp8", (64, 128), 1, (72, 128), 1, torch.float32, True),
+    ("fp8", (129, 192), 1, (140, 192), 1, torch.bfloat16, False),   # short last slab
+    ("fp8", (2, 3, 4, 8), 2, (7, 4, 8), 1, torch.float32, False),
+    ("fp8", (1, 5), 1, (1, 5), 1, torch.float32, False),
+    ("fp8", (256, 832), 1, (512, 832), 1, torch.float32, True),
 ]
 
 
@@ -119,7 +129,7 @@ def test_cartesian_dot(case):
     dtype, s0, n0, s1, n1, odt, relu = case
     k = int(np.prod(s0[n0:]))
     a0 = gen(dtype, s0, 1200 + s0[0], 1.0)
-    a1 = gen(dtype, s1, 1300 + s1[0], 1.0 / np.sqrt(k) if dtype == "bf16" else 1.0)
+    a1 = gen(dtype, s1, 1300 + s1[0], 1.0 / np.sqrt(k) if dtype in ("bf16", "fp8") else 1.0)
     got = gs.cartesian_dot(a0.to(DEV), a1.to(DEV), n0, n1, odt, gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE)
     prog = pg.cartesian_dot(ap.access(ap.tensor(to_oracle(a0)), n0), ap.access(ap.tensor(to_oracle(a1)), n1))
     if relu:
@@ -134,6 +144,24 @@ def test_cartesian_dot_extreme_int8_values():
     a1 = torch.full((33, 512), -128, dtype=torch.int8)
     got = gs.cartesian_dot(a0.to(DEV), a1.to(DEV))
     assert (got.cpu() == 128 * 128 * 512).all()
+
+
+def test_cartesian_dot_fp8_every_code():
+    """All 254 finite e4m3 codes (subnormals, -0, +-448) as operands: the hardware must read the
+    OCP encoding (bias 7, no infinities), not a variant with another bias or NaN placement."""
+    codes = np.arange(256, dtype=np.uint8)
+    codes[codes == 0x7F] = 0
+    codes[codes == 0xFF] = 0x80
+    a0 = torch.from_numpy(np.stack([np.roll(codes, r) for r in range(64)])).view(torch.float8_e4m3fn)
+    a1 = gen("fp8", (40, 256), 1777, 0.5)
+    for odt in (torch.float32, torch.bfloat16):
+        got = gs.cartesian_dot(a0.to(DEV), a1.to(DEV), 1, 1, odt)
+        assert_parity(got, brute.matmul(to_oracle(a0), to_oracle(a1).T), float_tol=1e-2, what=str(odt))
+    # one code at a time against 1.0: the products are the decoded values themselves
+    eye = torch.from_numpy(np.where(np.eye(256, dtype=bool), 0x38, 0).astype(np.uint8)).view(torch.float8_e4m3fn)
+    row = torch.from_numpy(np.tile(codes, (3, 1))).view(torch.float8_e4m3fn)
+    got = gs.cartesian_dot(row.to(DEV), eye.to(DEV), 1, 1, torch.float32).cpu().numpy().astype(np.float64)
+    np.testing.assert_array_equal(got, np.tile(to_oracle(row)[0], (3, 1)))
 
 
 def test_cartesian_dot_empty():
@@ -155,6 +183,9 @@ BIG_DOT_CASES = [
     ("bf16", 1800, 1804, 264 * 2, torch.float32, False), # 128x128, 4 columns per lane
     ("i8", 1801, 1803, 160, torch.int32, False),         # 128x128, one column per lane
     ("i8", 1800, 1808, 512, torch.int32, True),
+    ("fp8", 4100, 4104, 512, torch.bfloat16, True),      # 256x256, 8-bit floats
+    ("fp8", 4100, 4099, 192, torch.float32, False),      # short last slab
+    ("fp8", 1800, 1804, 576, torch.float32, False),      # 128x128
 ]
 
 
@@ -162,7 +193,7 @@ BIG_DOT_CASES = [
 def test_cartesian_dot_large_tiles(case):
     dtype, I, J, K, odt, relu = case
     a0 = gen(dtype, (I, K), 1400 + I + K, 1.0)
-    a1 = gen(dtype, (J, K), 1500 + J + K, 1.0 / np.sqrt(K) if dtype == "bf16" else 1.0)
+    a1 = gen(dtype, (J, K), 1500 + J + K, 1.0 / np.sqrt(K) if dtype in ("bf16", "fp8") else 1.0)
     got = gs.cartesian_dot(a0.to(DEV), a1.to(DEV), 1, 1, odt, gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE)
     rows = sorted({0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, 257, 1023, 1024, I // 2, I - 130, I - 5, I - 2, I - 1}
                   | set(int(v) for v in np.random.default_rng(I + J).integers(0, I, 40)))
@@ -538,6 +569,9 @@ def test_cartesian_dot_blocked_ragged_tiles(tiles):
     gotf = gs.cartesian_dot_blocked(b0.to(DEV), b1.to(DEV), *tiles)
     prog = pg.cartesian_dot(ap.access(ap.tensor(to_oracle(b0)), 1), ap.access(ap.tensor(to_oracle(b1)), 1))
     assert_parity(gotf, prog.materialize(), what=f"ragged {tiles}")
+    c0, c1 = gen("fp8", (150, 320), 2805), gen("fp8", (130, 320), 2806, 1.0 / np.sqrt(320))
+    got8 = gs.cartesian_dot_blocked(c0.to(DEV), c1.to(DEV), *tiles)
+    assert_parity(got8, brute.matmul(to_oracle(c0), to_oracle(c1).T), what=f"ragged fp8 {tiles}")
 
 
 def test_blocked_matmul_from_slices_and_concat():

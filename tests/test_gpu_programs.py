@@ -50,12 +50,16 @@ def test_conv2d_listing_on_padded_tensor():
     assert torch.equal(got, gs.conv2d_direct(cfg["x"].to(DEV), cfg["w"].to(DEV), (1, 1), (1, 1)))
 
 
-@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "fp8"])
 @pytest.mark.parametrize("dims", [(32, 32, 32), (70, 96, 200)])
 def test_matmul_listing_and_its_rewrites(dtype, dims):
     m, n, k = dims
-    a = synth.uniform_int8((m, k), -127, 127, 9500) if dtype == "i8" else synth.normal_bf16((m, k), 1.0, 9500)
-    w = synth.uniform_int8((k, n), -127, 127, 9501) if dtype == "i8" else synth.normal_bf16((k, n), k ** -0.5, 9501)
+    if dtype == "i8":
+        a, w = synth.uniform_int8((m, k), -127, 127, 9500), synth.uniform_int8((k, n), -127, 127, 9501)
+    elif dtype == "bf16":
+        a, w = synth.normal_bf16((m, k), 1.0, 9500), synth.normal_bf16((k, n), k ** -0.5, 9501)
+    else:
+        a, w = synth.normal_fp8((m, k), 1.0, 9500), synth.normal_fp8((k, n), k ** -0.5, 9501)
     tensors = {"activations": a, "weights": w}
     got, want = run_both(listings.MATMUL, tensors)
     ref = want.materialize()

@@ -268,6 +268,24 @@ def test_bf16_conversions_against_torch():
     assert numerics.bf16_bits_to_f64(numerics.f32_to_bf16_bits(np.float32(1 + 3 * 2 ** -8))) == 1 + 2 ** -6
 
 
+def test_e4m3_decode_against_torch_and_by_hand():
+    """Every one of the 256 bit patterns against torch's float8_e4m3fn -> float32 conversion, and the
+    values the OCP format fixes by definition."""
+    bits = np.arange(256, dtype=np.uint8)
+    got = numerics.e4m3_bits_to_f64(bits)
+    want = torch.from_numpy(bits.copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy().astype(np.float64)
+    np.testing.assert_array_equal(np.isnan(got), np.isnan(want))
+    ok = ~np.isnan(want)
+    np.testing.assert_array_equal(got[ok], want[ok])
+    by_hand = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x3C: 1.5,
+               0x40: 2.0, 0x7E: 448.0, 0xC0: -2.0, 0xB8: -1.0, 0xFE: -448.0}
+    for b, v in by_hand.items():
+        assert got[b] == v, hex(b)
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF]) and np.signbit(got[0x80]) and got[0x80] == 0.0
+    assert (np.diff(got[:0x7F]) > 0).all()          # positive patterns are ordered like their bits
+    np.testing.assert_array_equal(got[0x80:0xFF], -got[0x00:0x7F])
+
+
 def test_i32_check_refuses_overflow():
     assert numerics.to_i32_checked(np.array([2 ** 31 - 1, -2 ** 31])).dtype == np.int32
     with pytest.raises(OverflowError):
