@@ -307,6 +307,39 @@ class MaxPool(_Simple):
                 "sample": f"brute-force C loops (fp64, OpenMP) on the whole tensor, {dt:.2f} s"}
 
 
+class Depthwise(_Simple):
+    """Depth-wise windows: (32,128,112,112) bf16, one 3x3 filter per channel, stride 1, pad 1."""
+
+    name = "depth-wise 3x3 s1 p1 on (32,128,112,112) bf16 -> bf16 (one filter per channel)"
+    dominant = "depthwise_kernel"
+
+    def __init__(self, dev):
+        from paper_2105_09377_amd import binding as gs, synth
+        self.gs = gs
+        self.x = synth.normal_bf16((32, 128, 112, 112), 1.0, 7601)
+        self.w = synth.normal_bf16((128, 3, 3), 1.0 / 3.0, 7602)
+        self.work = 2 * self.x.numel() * 2 + self.w.numel() * 2
+        self.nsets = self._sets(self.work, 6)
+        self.xs = [self.x.to(dev).clone() for _ in range(self.nsets)]
+        self.wd = self.w.to(dev)
+        self.outs = [torch.empty((32, 128, 112, 112), dtype=torch.bfloat16, device=dev) for _ in range(self.nsets)]
+
+    def step(self, i):
+        self.gs.depthwise_conv2d(self.xs[i], self.wd, (1, 1), (1, 1), out=self.outs[i])
+
+    def cpu_baseline(self):
+        import numpy as np
+        from oracle import brute
+        n = 8
+        x, w = _bf16_to_f64(self.x[:n]), _bf16_to_f64(self.w)
+        t0 = time.perf_counter()
+        for c in range(128):       # channel c against filter c: the one-channel program of Fig. 2a
+            brute.conv2d(np.ascontiguousarray(x[:, c:c + 1]), np.ascontiguousarray(w[c:c + 1, None]), (1, 1), (1, 1))
+        dt = time.perf_counter() - t0
+        return {"value": self.work * n / 32 / dt / 1e9, "unit": "GB/s", "cores": brute.num_threads(), "kind": "oracle",
+                "sample": f"brute-force C loops (fp64, OpenMP), channel by channel, on {n} of the 32 images, {dt:.2f} s"}
+
+
 class Transpose(_Simple):
     """transpose (0 3 1 2): the (N,H',W',O) -> (N,O,H',W') tail of the im2col convolution listing,
     at the size of the stack's stage-1 result (batch 64), bf16."""
@@ -546,7 +579,7 @@ class MlpScaled(Mlp):
 
 
 WORKLOADS = {"conv3x3": Conv3x3, "conv3x3_b64": Conv3x3Batch64, "conv3x3_i8": Conv3x3Int8, "resnet18": ResNet18, "im2col_gather": Im2colGather, "maxpool": MaxPool,
-             "reduce": RowReduce, "transpose": Transpose, "dense": DenseBig, "dense_i8": DenseInt8, "dense_fp8": DenseFp8, "dense_blocked": DenseBlocked, "mlp": Mlp, "mlp_scaled": MlpScaled}
+             "reduce": RowReduce, "transpose": Transpose, "depthwise": Depthwise, "dense": DenseBig, "dense_i8": DenseInt8, "dense_fp8": DenseFp8, "dense_blocked": DenseBlocked, "mlp": Mlp, "mlp_scaled": MlpScaled}
 
 
 def main():

@@ -19,6 +19,9 @@
  *   - Element types: GS_I8 and GS_BF16 inputs to contractions accumulate in int32 and fp32
  *     respectively (exact for integers, no saturation; the paper's own notation is real-valued
  *     and fixes no storage type).  bfloat16 stores round to nearest even.
+ *   - A result never shares bytes with an input (nothing works in place).  The data-moving
+ *     transformers and glenside_depthwise_conv2d check this (partial overlap included) and return
+ *     GS_ERR_UNSUPPORTED; for the other entry points it is the caller's duty.
  *   - Extensions that the paper does not have are marked EXT: padding, ReLU, scaling, a fused
  *     residual input.  With pad = 0, act = GS_ACT_NONE, scale = 1 and residual = NULL every entry
  *     point computes exactly the paper's expression.
@@ -123,6 +126,19 @@ int glenside_conv2d_direct(const gs_ap* activations, const gs_ap* weights, const
 int glenside_conv2d_im2col(const gs_ap* activations, const gs_ap* weights, const int64_t stride[2],
                            const int64_t pad[2], const gs_ap* residual, int act, gs_ap* out,
                            void* workspace, size_t workspace_bytes, void* stream);
+/* Depth-wise windows (EXT workload, written with the paper's operators only): the concat along
+ * the channel dimension of the program of Fig. 2a applied, for every channel c, to
+ * (slice activations 1 c c+1) and (slice weights' 0 c c+1) -- C independent one-channel, one-filter
+ * convolutions; with windows of shape (1,Kh,Kw) no sum over channels is left (Table 1, windows).
+ * activations ((N),(C,H,W)), weights ((C),(Kh,Kw)) -> out ((N,C,H',W'),()):
+ *   out[n,c,y,x] = sum_{ky,kx} activations[n,c, y*Sh - Ph + ky, x*Sw - Pw + kx] * weights[c,ky,kx],
+ * cells outside the image counting as zero (EXT pad[2], symmetric, each smaller than its window
+ * dimension); act applies ReLU.  Types: i8 x i8 -> i32; bf16 x bf16 -> bf16 or f32 (fp32
+ * accumulate, taps in the order ky, kx).  No workspace.  Windows or strides above 64, or rows too
+ * long for the on-chip copy (about 16000 elements), return GS_ERR_UNSUPPORTED.                   */
+int glenside_depthwise_conv2d(const gs_ap* activations, const gs_ap* weights, const int64_t stride[2],
+                              const int64_t pad[2], int act, gs_ap* out, void* stream);
+
 /* The two halves of glenside_conv2d_direct, for callers whose weights are constants.
  *   _pack_weights  : writes the weight access pattern ((O),(C,Kh,Kw)) into `packed` in the order
  *                    the contraction reads it, (O, Kh, Kw, C) with C padded to a 32-byte step --

@@ -43,6 +43,21 @@ def conv2d(activations: ap.AP, weights: ap.AP, stride: Sequence[int],
     return ap.transpose(ap.squeeze(dp, 1), (0, 3, 1, 2))
 
 
+def depthwise_conv2d(activations: ap.AP, weights: ap.AP, stride: Sequence[int],
+                     pad_hw: Sequence[int] = (0, 0)) -> ap.AP:
+    """Depth-wise windows, written with Table 1 / Table 2 operators only: activations (N,C,H,W),
+    weights (C,1,Kh,Kw) -> ((N,C,H',W'),()).  Channel c of the activations and filter c of the
+    weights are cut out with `slice`, put through the program of Fig. 2a (a one-channel,
+    one-filter convolution), and the C results are joined with `concat` along dimension 1."""
+    c = activations.shape[1]
+    assert weights.shape[0] == c and weights.shape[1] == 1
+    result = None
+    for ch in range(c):
+        one = conv2d(ap.slice_(activations, 1, ch, ch + 1), ap.slice_(weights, 0, ch, ch + 1), stride, pad_hw)
+        result = one if result is None else ap.concat(result, one, 1)
+    return result
+
+
 def conv2d_im2col(activations: ap.AP, weights: ap.AP, stride: Sequence[int],
                   pad_hw: Sequence[int] = (0, 0)) -> ap.AP:
     """Fig. 5: the im2col form; `?shape` is the shape of the direct form's dotProd result."""

@@ -37,7 +37,7 @@ EXPORTS = (
     "glenside_pad", "glenside_pair", "glenside_cartesian_dot_blocked",
     "glenside_conv2d_direct_static", "glenside_conv2d_direct_static_limit",
     "glenside_program_shape", "glenside_program_eval", "glenside_program_workspace",
-    "glenside_program_rewrite",
+    "glenside_program_rewrite", "glenside_depthwise_conv2d",
 )
 
 
@@ -228,6 +228,19 @@ def conv2d_direct(x, w, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NON
     """Fig. 2a with the windows formed on chip; x (N,C,H,W), w (O,C,Kh,Kw) -> (N,O,H',W')."""
     return _conv("glenside_conv2d_direct", "glenside_conv2d_direct_workspace", x, w, stride, pad,
                  residual, act, out_dtype, out, workspace)
+
+
+def depthwise_conv2d(x, w, stride=(1, 1), pad=(0, 0), act=GS_ACT_NONE, out_dtype=None, out=None) -> torch.Tensor:
+    """Every channel convolved with its own filter: x (N,C,H,W), w (C,Kh,Kw) -> (N,C,H',W')."""
+    if out is None:
+        if out_dtype is None:
+            out_dtype = torch.int32 if x.dtype == torch.int8 else torch.float32
+        shape, _ = windows_out_shape(x.shape, 2, (w.shape[1], w.shape[2]), tuple(stride), tuple(pad), tuple(pad))
+        out = torch.empty(tuple(shape[:4]), dtype=out_dtype, device=x.device)
+    _check(lib().glenside_depthwise_conv2d(ctypes.byref(make_ap(x, 1)), ctypes.byref(make_ap(w, 1)),
+                                           _i64(stride), _i64(pad), act, ctypes.byref(make_ap(out, 4)),
+                                           _stream(x)), "depthwise_conv2d")
+    return out
 
 
 def conv2d_direct_static(x, w, stride=(1, 1), pad=(0, 0), residual=None, act=GS_ACT_NONE, out_dtype=None,

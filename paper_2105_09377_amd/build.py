@@ -16,7 +16,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-i
 # (source, object, extra defines).  The pipelined convolution kernel is instantiated once per
 # element type and tile shape, each in its own object so that they compile in parallel.
 UNITS = [(src, os.path.splitext(src)[0] + ".o", []) for src in
-         ("api.hip", "program.hip", "windows.hip", "gemm.hip", "conv.hip", "conv_smallc.hip", "reduce.hip", "move.hip")]
+         ("api.hip", "program.hip", "windows.hip", "gemm.hip", "conv.hip", "conv_smallc.hip", "reduce.hip", "move.hip", "depthwise.hip")]
 for _tr, _tag in (("Bf16Traits", "bf16"), ("I8Traits", "i8")):
     for _tile in range(3):
         UNITS.append(("conv3_inst.hip", f"conv3_{_tag}_t{_tile}.o",

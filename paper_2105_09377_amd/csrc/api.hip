@@ -49,6 +49,14 @@ bool same_shape(const gs_ap* a, const gs_ap* b) {
   return true;
 }
 
+// Do the bytes of two access patterns overlap?  (Empty tensors overlap nothing.)
+bool overlaps(const gs_ap* a, const gs_ap* b) {
+  const uint64_t na = uint64_t(numel(a)) * dtype_size(a->dtype), nb = uint64_t(numel(b)) * dtype_size(b->dtype);
+  if (na == 0 || nb == 0) return false;
+  const uintptr_t pa = reinterpret_cast<uintptr_t>(a->data), pb = reinterpret_cast<uintptr_t>(b->data);
+  return pa < pb + nb && pb < pa + na;
+}
+
 uint32_t lowest_bits(int dtype) {
   switch (dtype) {
     case GS_I8: return 0x80u;
@@ -563,6 +571,48 @@ int glenside_reduce(const gs_ap* in, int op, float scale, gs_ap* out, void* stre
   return launch_status(launch_reduce(a, static_cast<hipStream_t>(stream)));
 }
 
+int glenside_depthwise_conv2d(const gs_ap* act, const gs_ap* w, const int64_t stride[2],
+                              const int64_t pad[2], int act_fn, gs_ap* out, void* stream) {
+  int st = check_ap(act, true);
+  if (st) return st;
+  st = check_ap(w, true);
+  if (st) return st;
+  st = check_ap(out, true);
+  if (st) return st;
+  if (!stride || !pad) return GS_ERR_NULL;
+  if (act->rank != 4 || act->n_access != 1 || w->rank != 3 || w->n_access != 1) return GS_ERR_RANK;
+  if (out->rank != 4 || out->n_access != 4) return GS_ERR_RANK;
+  if (act_fn != GS_ACT_NONE && act_fn != GS_ACT_RELU) return GS_ERR_UNSUPPORTED;
+  if (act->dtype != w->dtype) return GS_ERR_DTYPE;
+  if (act->dtype == GS_I8) {
+    if (out->dtype != GS_I32) return GS_ERR_DTYPE;
+  } else if (act->dtype == GS_BF16) {
+    if (out->dtype != GS_BF16 && out->dtype != GS_F32) return GS_ERR_DTYPE;
+  } else {
+    return GS_ERR_DTYPE;
+  }
+  const int64_t N = act->shape[0], C = act->shape[1], H = act->shape[2], W = act->shape[3];
+  const int64_t Kh = w->shape[1], Kw = w->shape[2];
+  if (w->shape[0] != C) return GS_ERR_SHAPE;
+  if (stride[0] < 1 || stride[1] < 1 || pad[0] < 0 || pad[1] < 0 || Kh < 1 || Kw < 1) return GS_ERR_SHAPE;
+  if (H + 2 * pad[0] < Kh || W + 2 * pad[1] < Kw) return GS_ERR_SHAPE;
+  const int64_t Ho = (H + 2 * pad[0] - Kh) / stride[0] + 1, Wo = (W + 2 * pad[1] - Kw) / stride[1] + 1;
+  if (out->shape[0] != N || out->shape[1] != C || out->shape[2] != Ho || out->shape[3] != Wo)
+    return GS_ERR_SHAPE;
+  if (N > (1 << 24) || C > (1 << 24) || H > (1 << 20) || W > (1 << 20) || Kh > 64 || Kw > 64 ||
+      stride[0] > 64 || stride[1] > 64 || pad[0] >= Kh || pad[1] >= Kw)
+    return GS_ERR_UNSUPPORTED;
+  if (overlaps(act, out) || overlaps(w, out)) return GS_ERR_UNSUPPORTED;
+  DepthwiseArgs d;
+  memset(&d, 0, sizeof(d));
+  d.in = act->data; d.w = w->data; d.out = out->data;
+  d.in_dtype = act->dtype; d.out_dtype = out->dtype; d.relu = act_fn == GS_ACT_RELU;
+  d.N = int(N); d.C = int(C); d.H = int(H); d.W = int(W); d.Ho = int(Ho); d.Wo = int(Wo);
+  d.Kh = int(Kh); d.Kw = int(Kw); d.Sh = int(stride[0]); d.Sw = int(stride[1]);
+  d.Ph = int(pad[0]); d.Pw = int(pad[1]);
+  return launch_status(launch_depthwise(d, static_cast<hipStream_t>(stream)));
+}
+
 int glenside_windows_reduce(const gs_ap* in, const int64_t* window, const int64_t* stride,
                             const int64_t* pad_lo, const int64_t* pad_hi, int op, float scale,
                             gs_ap* out, void* stream) {
@@ -662,6 +712,7 @@ void row_major_strides(const gs_ap* a, int64_t* st) {
 // A box copy between two dense tensors: dims/strides given in the output's dimension order.
 int run_move(const gs_ap* in, gs_ap* out, int rank, const int64_t* dims, const int64_t* is,
              const int64_t* os, int64_t in_off, int64_t out_off, void* stream) {
+  if (overlaps(in, out)) return GS_ERR_UNSUPPORTED;    // a mover reads while it writes: never in place
   MoveArgs m;
   memset(&m, 0, sizeof(m));
   m.in = in->data;
@@ -695,7 +746,7 @@ int glenside_transpose(const gs_ap* in, const int64_t* perm, gs_ap* out, void* s
   if (st) return st;
   st = check_ap(out, true);
   if (st) return st;
-  if ((out->data && out->data == in->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (overlaps(in, out)) return GS_ERR_UNSUPPORTED;   // the result must not share bytes with an input
   if (!perm) return GS_ERR_NULL;
   bool seen[GS_MAX_RANK] = {false};
   int64_t shape[GS_MAX_RANK], ist[GS_MAX_RANK], is[GS_MAX_RANK], os[GS_MAX_RANK];
@@ -717,7 +768,7 @@ int glenside_slice(const gs_ap* in, int dim, int64_t lo, int64_t hi, gs_ap* out,
   if (st) return st;
   st = check_ap(out, true);
   if (st) return st;
-  if ((out->data && out->data == in->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (overlaps(in, out)) return GS_ERR_UNSUPPORTED;   // the result must not share bytes with an input
   if (dim < 0 || dim >= in->rank) return GS_ERR_RANK;
   if (lo < 0 || lo > hi || hi > in->shape[dim]) return GS_ERR_SHAPE;
   int64_t shape[GS_MAX_RANK], is[GS_MAX_RANK], os[GS_MAX_RANK];
@@ -737,7 +788,7 @@ int glenside_concat(const gs_ap* a, const gs_ap* b, int dim, gs_ap* out, void* s
   if (st) return st;
   st = check_ap(out, true);
   if (st) return st;
-  if ((out->data && out->data == a->data) || (out->data && out->data == b->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (overlaps(a, out) || overlaps(b, out)) return GS_ERR_UNSUPPORTED;   // the result must not share bytes with an input
   if (a->rank != b->rank || a->n_access != b->n_access) return GS_ERR_RANK;
   if (dim < 0 || dim >= a->rank) return GS_ERR_RANK;
   if (a->dtype != b->dtype) return GS_ERR_DTYPE;
@@ -763,7 +814,7 @@ int glenside_pad(const gs_ap* in, int dim, int64_t lo, int64_t hi, int pad_mode,
   if (st) return st;
   st = check_ap(out, true);
   if (st) return st;
-  if ((out->data && out->data == in->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (overlaps(in, out)) return GS_ERR_UNSUPPORTED;   // the result must not share bytes with an input
   if (dim < 0 || dim >= in->rank) return GS_ERR_RANK;
   if (lo < 0 || hi < 0) return GS_ERR_SHAPE;
   if (pad_mode != GS_PAD_ZERO && pad_mode != GS_PAD_LOWEST) return GS_ERR_UNSUPPORTED;
@@ -790,7 +841,7 @@ int glenside_pair(const gs_ap* a, const gs_ap* b, gs_ap* out, void* stream) {
   if (st) return st;
   st = check_ap(out, true);
   if (st) return st;
-  if ((out->data && out->data == a->data) || (out->data && out->data == b->data)) return GS_ERR_UNSUPPORTED;   // the result must be a distinct tensor
+  if (overlaps(a, out) || overlaps(b, out)) return GS_ERR_UNSUPPORTED;   // the result must not share bytes with an input
   if (a->rank != b->rank || a->n_access != b->n_access) return GS_ERR_RANK;
   if (!same_shape(a, b)) return GS_ERR_SHAPE;
   if (a->dtype != b->dtype) return GS_ERR_DTYPE;

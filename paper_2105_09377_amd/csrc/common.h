@@ -311,6 +311,15 @@ struct WindowsReduceArgs {
 };
 hipError_t launch_windows_reduce(const WindowsReduceArgs& a, hipStream_t s);
 
+struct DepthwiseArgs {    // out[n][c][y][x] = sum_{ky,kx} in[n][c][y*Sh-Ph+ky][x*Sw-Pw+kx] * w[c][ky][kx]
+  const void* in;
+  const void* w;
+  void* out;
+  int in_dtype, out_dtype, relu;
+  int N, C, H, W, Ho, Wo, Kh, Kw, Sh, Sw, Ph, Pw;
+};
+hipError_t launch_depthwise(const DepthwiseArgs& a, hipStream_t s);
+
 struct PairArgs {
   const void* a;
   const void* b;

@@ -161,6 +161,44 @@ def test_transformer_validation():
     assert pr(full, full, ap((1,) * 8, 4, data=other)) == gs.GS_ERR_RANK              # rank 9 does not exist
 
 
+def test_results_that_overlap_an_input_are_refused():
+    """Partial overlaps, not only equal pointers: x is 4*5*6 bfloat16 = 240 bytes at FAKE."""
+    L = gs.lib()
+    x = ap((4, 5, 6), 1)
+    for delta in (16, 224, -16):                              # the result starts inside / ends inside x
+        at = FAKE + delta
+        assert L.glenside_transpose(ctypes.byref(x), i64(2, 0, 1), ctypes.byref(ap((6, 4, 5), 1, data=at)), None) == gs.GS_ERR_UNSUPPORTED
+        assert L.glenside_slice(ctypes.byref(x), 1, 1, 3, ctypes.byref(ap((4, 2, 6), 1, data=at)), None) == gs.GS_ERR_UNSUPPORTED
+        assert L.glenside_pad(ctypes.byref(x), 2, 1, 1, gs.GS_PAD_ZERO, ctypes.byref(ap((4, 5, 8), 1, data=at)), None) == gs.GS_ERR_UNSUPPORTED
+        b = ap((4, 2, 6), 1, data=0x40000)
+        assert L.glenside_concat(ctypes.byref(x), ctypes.byref(b), 1, ctypes.byref(ap((4, 7, 6), 1, data=at)), None) == gs.GS_ERR_UNSUPPORTED
+        assert L.glenside_concat(ctypes.byref(b), ctypes.byref(x), 1, ctypes.byref(ap((4, 7, 6), 1, data=at)), None) == gs.GS_ERR_UNSUPPORTED
+        y = ap((4, 5, 6), 1, data=0x40000)
+        assert L.glenside_pair(ctypes.byref(y), ctypes.byref(x), ctypes.byref(ap((4, 2, 5, 6), 1, data=at)), None) == gs.GS_ERR_UNSUPPORTED
+
+
+def test_depthwise_validation():
+    L = gs.lib()
+    x, w = ap((2, 8, 14, 14), 1), ap((8, 3, 3), 1)
+    other = 0x80000
+    dw = lambda a, f, s, p, out, act=gs.GS_ACT_NONE: L.glenside_depthwise_conv2d(
+        ctypes.byref(a), ctypes.byref(f), i64(*s), i64(*p), act, ctypes.byref(out), None)
+    good = ap((2, 8, 14, 14), 4, data=other)
+    assert dw(x, ap((7, 3, 3), 1), (1, 1), (1, 1), good) == gs.GS_ERR_SHAPE            # one filter per channel
+    assert dw(x, ap((8, 1, 3, 3), 1), (1, 1), (1, 1), good) == gs.GS_ERR_RANK
+    assert dw(x, w, (1, 1), (1, 1), ap((2, 8, 12, 12), 4, data=other)) == gs.GS_ERR_SHAPE
+    assert dw(x, w, (2, 2), (1, 1), ap((2, 8, 7, 7), 1, data=other)) == gs.GS_ERR_RANK  # the result is all access dims
+    assert dw(x, w, (0, 1), (1, 1), good) == gs.GS_ERR_SHAPE
+    assert dw(x, w, (1, 1), (3, 3), ap((2, 8, 18, 18), 4, data=other)) == gs.GS_ERR_UNSUPPORTED   # padding >= window
+    assert dw(x, w, (1, 1), (1, 1), ap((2, 8, 14, 14), 4, gs.GS_I32, data=other)) == gs.GS_ERR_DTYPE
+    assert dw(x, ap((8, 3, 3), 1, gs.GS_I8), (1, 1), (1, 1), good) == gs.GS_ERR_DTYPE
+    assert dw(ap((2, 8, 14, 14), 1, gs.GS_F32), ap((8, 3, 3), 1, gs.GS_F32), (1, 1), (1, 1),
+              ap((2, 8, 14, 14), 4, gs.GS_F32, data=other)) == gs.GS_ERR_DTYPE
+    assert dw(x, w, (1, 1), (1, 1), good, act=9) == gs.GS_ERR_UNSUPPORTED
+    assert dw(x, w, (1, 1), (1, 1), ap((2, 8, 14, 14), 4, data=FAKE + 64)) == gs.GS_ERR_UNSUPPORTED   # overlaps x
+    assert dw(ap((2, 8, 2, 14), 1), w, (1, 1), (0, 0), ap((2, 8, 0, 12), 4, data=other)) == gs.GS_ERR_SHAPE  # window taller than the image
+
+
 def test_blocked_dot_validation():
     L = gs.lib()
     call = lambda a0, a1, tm, tn, tk, out: L.glenside_cartesian_dot_blocked(

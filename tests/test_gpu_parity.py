@@ -591,3 +591,72 @@ def test_blocked_matmul_from_slices_and_concat():
     assert torch.equal(blocked, whole)
     prog = pg.cartesian_dot(ap.access(ap.tensor(to_oracle(a)), 1), ap.access(ap.tensor(to_oracle(b)), 1))
     assert_parity(blocked, prog.materialize(), what="blocked matmul")
+
+
+# ---------------------------------------------------------------------------------------------
+# depth-wise windows
+# ---------------------------------------------------------------------------------------------
+
+def oracle_depthwise(x, w, stride, pad):
+    """C one-channel convolutions (brute-force loops), stacked along the channel dimension."""
+    xo, wo = to_oracle(x), to_oracle(w)
+    return np.concatenate([brute.conv2d(np.ascontiguousarray(xo[:, c:c + 1]), np.ascontiguousarray(wo[c:c + 1, None]),
+                                        stride, pad) for c in range(x.shape[1])], axis=1)
+
+
+def test_depthwise_is_the_sliced_program():
+    """Small case against the program itself: slice / Fig. 2a / concat, evaluated by the interpreter."""
+    for dtype, odt in (("bf16", torch.float32), ("i8", torch.int32)):
+        x, w = gen(dtype, (2, 5, 9, 11), 3101), gen(dtype, (5, 3, 3), 3102, 0.3)
+        got = gs.depthwise_conv2d(x.to(DEV), w.to(DEV), (1, 1), (1, 1), out_dtype=odt)
+        prog = pg.depthwise_conv2d(ap.tensor(to_oracle(x)), ap.tensor(to_oracle(w)[:, None]), (1, 1), (1, 1))
+        assert tuple(got.shape) == prog.access_shape
+        assert_parity(got, prog.materialize(), what=f"depth-wise program {dtype}")
+
+
+DEPTHWISE_CASES = [
+    # dtype, N, C, H, W, Kh, Kw, stride, pad, out dtype, relu
+    ("bf16", 3, 24, 56, 56, 3, 3, (1, 1), (1, 1), torch.bfloat16, False),   # several planes per task, 16-byte stores
+    ("bf16", 2, 16, 112, 112, 3, 3, (2, 2), (1, 1), torch.bfloat16, True),  # one plane per task, stride 2
+    ("bf16", 1, 3, 300, 200, 3, 3, (1, 1), (1, 1), torch.float32, False),   # planes cut into bands of rows
+    ("bf16", 1, 2, 301, 203, 3, 3, (2, 2), (1, 1), torch.bfloat16, False),  # bands, stride 2, odd sizes
+    ("bf16", 4, 40, 14, 14, 3, 3, (1, 1), (1, 1), torch.bfloat16, True),    # rows that are no multiple of 16 bytes
+    ("bf16", 5, 67, 7, 7, 3, 3, (1, 1), (1, 1), torch.float32, False),      # ragged last group of planes
+    ("bf16", 2, 6, 28, 28, 3, 3, (2, 2), (1, 1), torch.bfloat16, False),
+    ("bf16", 2, 7, 13, 17, 5, 5, (1, 1), (2, 2), torch.float32, True),      # 5x5
+    ("bf16", 2, 3, 20, 19, 3, 2, (2, 1), (1, 0), torch.float32, False),     # run-time window loops
+    ("bf16", 2, 3, 9, 9, 1, 1, (1, 1), (0, 0), torch.bfloat16, False),      # 1x1: a per-channel scale
+    ("bf16", 1, 1, 3, 3, 3, 3, (1, 1), (0, 0), torch.float32, False),       # a single window
+    ("i8", 3, 24, 56, 56, 3, 3, (1, 1), (1, 1), torch.int32, False),
+    ("i8", 2, 9, 112, 112, 3, 3, (2, 2), (1, 1), torch.int32, True),
+    ("i8", 4, 33, 14, 14, 3, 3, (1, 1), (1, 1), torch.int32, False),
+    ("i8", 1, 2, 200, 333, 5, 5, (1, 1), (2, 2), torch.int32, False),
+    ("i8", 2, 3, 20, 19, 4, 3, (3, 2), (0, 2), torch.int32, False),
+]
+
+
+@pytest.mark.parametrize("case", DEPTHWISE_CASES)
+def test_depthwise_conv2d(case):
+    dtype, n, c, h, w_, kh, kw, stride, pad, odt, relu = case
+    x = gen(dtype, (n, c, h, w_), 3200 + c + h)
+    w = gen(dtype, (c, kh, kw), 3300 + c + kh, 1.0 / np.sqrt(kh * kw) if dtype == "bf16" else 1.0)
+    got = gs.depthwise_conv2d(x.to(DEV), w.to(DEV), stride, pad, gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE, odt)
+    want = oracle_depthwise(x, w, stride, pad)
+    if relu:
+        want = np.maximum(want, 0)
+    assert_parity(got, want, what=str(case))
+
+
+def test_depthwise_extremes_and_empty():
+    x = torch.full((2, 3, 10, 10), -128, dtype=torch.int8)
+    w = torch.full((3, 3, 3), -128, dtype=torch.int8)
+    got = gs.depthwise_conv2d(x.to(DEV), w.to(DEV), (1, 1), (0, 0))
+    assert (got.cpu() == 128 * 128 * 9).all()
+    # an infinity next to the border must not leak into windows that do not contain it
+    xf = torch.zeros((1, 1, 8, 8), dtype=torch.bfloat16)
+    xf[0, 0, 0, 7] = float("inf")
+    wf = torch.ones((1, 3, 3), dtype=torch.bfloat16)
+    gf = gs.depthwise_conv2d(xf.to(DEV), wf.to(DEV), (1, 1), (1, 1)).cpu()
+    assert torch.isinf(gf[0, 0, :2, 6:]).all() and torch.isfinite(gf[0, 0, 2:]).all() and torch.isfinite(gf[0, 0, :, :6]).all()
+    empty = torch.zeros((0, 4, 8, 8), dtype=torch.bfloat16, device=DEV)
+    assert gs.depthwise_conv2d(empty, torch.ones((4, 3, 3), dtype=torch.bfloat16, device=DEV), (1, 1), (1, 1)).shape == (0, 4, 8, 8)

@@ -252,6 +252,34 @@ def test_sampled_positions_equal_full_evaluation():
     assert prog.at(1, 4, 2, 3) == full[1, 4, 2, 3]
 
 
+def test_depthwise_program_against_block_diagonal_convolution_and_closed_forms():
+    """The depth-wise program (slice / Fig. 2a / concat) equals an ordinary convolution whose
+    weights are zero off the channel diagonal, equals explicit loops, and a one-hot filter tap
+    copies the shifted, strided channel."""
+    r = rng(61)
+    n, c, h, w, kh, kw = 2, 5, 9, 8, 3, 2
+    x = r.integers(-9, 10, (n, c, h, w))
+    f = r.integers(-9, 10, (c, 1, kh, kw))
+    for stride, pad in (((1, 1), (0, 0)), ((2, 1), (1, 1)), ((2, 3), (2, 0))):
+        got = pg.depthwise_conv2d(ap.tensor(x), ap.tensor(f), stride, pad).materialize()
+        full = np.zeros((c, c, kh, kw), dtype=np.int64)
+        for ch in range(c):
+            full[ch, ch] = f[ch, 0]
+        np.testing.assert_array_equal(got, brute.conv2d(x, full, stride, pad))
+        xp = np.pad(x, ((0, 0), (0, 0), (pad[0], pad[0]), (pad[1], pad[1])))
+        ho, wo = (h + 2 * pad[0] - kh) // stride[0] + 1, (w + 2 * pad[1] - kw) // stride[1] + 1
+        assert got.shape == (n, c, ho, wo)
+        for (i, ch, y, xx) in [(0, 0, 0, 0), (1, 4, ho - 1, wo - 1), (1, 2, ho // 2, 1)]:
+            want = sum(int(xp[i, ch, y * stride[0] + a, xx * stride[1] + b]) * int(f[ch, 0, a, b])
+                       for a in range(kh) for b in range(kw))
+            assert got[i, ch, y, xx] == want
+    tap = np.zeros((c, 1, kh, kw), dtype=np.int64)
+    tap[:, 0, 2, 1] = np.arange(1, c + 1)                 # channel ch: (ch + 1) * x[.., y*2 + 2, x + 1]
+    got = pg.depthwise_conv2d(ap.tensor(x), ap.tensor(tap), (2, 1), (0, 0)).materialize()
+    want = x[:, :, 2::2, 1:][:, :, :got.shape[2], :got.shape[3]] * np.arange(1, c + 1)[None, :, None, None]
+    np.testing.assert_array_equal(got, want)
+
+
 # -- storage-type conversions ------------------------------------------------------
 
 def test_bf16_conversions_against_torch():
