@@ -107,6 +107,7 @@ def lib() -> ctypes.CDLL:
         L.glenside_pad.argtypes = [ap_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ap_p, vp]
         L.glenside_pair.argtypes = [ap_p, ap_p, ap_p, vp]
         L.glenside_cartesian_dot_blocked.argtypes = [ap_p, ap_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ap_p, vp]
+        L.glenside_depthwise_conv2d.argtypes = [ap_p, ap_p, i64_p, i64_p, ctypes.c_int, ap_p, vp]
         _lib = L
     return _lib
 

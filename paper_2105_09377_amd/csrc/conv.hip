@@ -117,13 +117,13 @@ template <typename TR, int TO, int TP, int WO, int WP, int CB>
 static hipError_t launch_conv_cfg(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes,
                                   hipStream_t s) {
   auto kern = conv_direct_kernel<TR, TO, TP, WO, WP, CB>;
-  static size_t attr_bytes = 0;
-  if (lds_bytes > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
-    if (e != hipSuccess) return e;
-    attr_bytes = kLdsLimit;
-  }
+  static std::once_flag once;
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(once, [&]() {
+    attr_status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const int64_t tiles = ceil_div(g.M, TP) * ceil_div(a.O, TO);
   if (tiles > 0x7fffffff) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3(unsigned(tiles)), dim3(256), lds_bytes, s, a, g);

@@ -3,6 +3,8 @@
 // -DGS_CONV3_TRAITS / -DGS_CONV3_TILE / -DGS_CONV3_NAME (see build.py).
 #include "conv4_kernel.h"
 
+#include <mutex>
+
 namespace gs {
 
 // Pipelined kernel launcher: returns hipErrorInvalidValue when this shape does not fit it.
@@ -19,13 +21,13 @@ static hipError_t launch_conv3_cfg(const ConvArgs& a, ConvGeom g, hipStream_t s)
   const size_t lds_bytes = 1024 + 3 * size_t(a.Kh * a.Kw) * TO * 32 + patch_bytes;
   if (lds_bytes > size_t(kLdsLimit)) return hipErrorInvalidValue;
   auto kern = conv_direct3_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, D>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::once_flag once;              // the attribute is set once, whichever thread comes first
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(once, [&]() {
+    attr_status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const int64_t tiles = ceil_div(g.M, TP) * ceil_div(a.O, TO);
   const int64_t per_cu = lds_bytes <= size_t(kLdsLimit) / 2 ? 2 : 1;
   const int64_t grid = tiles < per_cu * conv_num_cus() ? tiles : per_cu * conv_num_cus();
@@ -39,13 +41,13 @@ template <typename TR, int TO, int TP, int WO, int WP, int VW, int KH, int KW, i
 static hipError_t launch_conv4_ring(const ConvArgs& a, const ConvGeom& g, size_t lds_bytes, hipStream_t s) {
   constexpr int NWB = TO <= 64 ? 3 : 2;
   auto kern = conv_direct4_kernel<TR, TO, TP, WO, WP, VW, KH, KW, MAXI, NWB, D, FLAT>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::once_flag once;              // the attribute is set once, whichever thread comes first
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(once, [&]() {
+    attr_status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsLimit));
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const int64_t tiles = ceil_div(g.M, g.tps) * ceil_div(a.O, TO) * (a.ksplit > 1 ? a.ksplit : 1);
   const int64_t grid = tiles < conv_num_cus() ? tiles : conv_num_cus();
   hipLaunchKernelGGL(kern, dim3(unsigned(grid)), dim3(512), lds_bytes, s, a, g);

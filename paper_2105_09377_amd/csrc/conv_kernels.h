@@ -287,13 +287,8 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(ConvArgs a, ConvGeom g
 typedef __attribute__((address_space(1))) const void* conv_gptr_t;
 typedef __attribute__((address_space(3))) void* conv_lptr_t;
 
-#ifdef GS_CONV3_SYNCTHREADS   // experiment: plain barriers that also drain global loads
-#define CONV3_BARRIER() __syncthreads()
-#define CONV3_WAIT() ((void)0)
-#else
 #define CONV3_BARRIER() lds_barrier()
 #define CONV3_WAIT() wait_vmem<kWaitWeights>()
-#endif
 
 // Same table as build_segments, built by the first lanes of a wave in parallel: lane s fills
 // segment s, lane 0 then turns the row counts into prefix sums.  Call with tid < 64.

@@ -26,6 +26,8 @@
 
 #include <limits.h>
 
+#include <mutex>
+
 namespace gs {
 
 struct SmallCArgs {
@@ -443,13 +445,13 @@ static hipError_t launch_smallc_t(const ConvArgs& a, hipStream_t s) {
   p.dKw = FastDiv::make(uint32_t(a.Kw));
   p.dchunk = FastDiv::make(uint32_t(p.Kp / EPV));
   auto kern = dr ? conv_smallc_kernel<TR, true> : conv_smallc_kernel<TR, false>;
-  static bool attr_done[2] = {false, false};
-  if (!attr_done[dr]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-    if (e != hipSuccess) return e;
-    attr_done[dr] = true;
-  }
+  static std::once_flag once[2];
+  static hipError_t attr_status[2] = {hipSuccess, hipSuccess};
+  std::call_once(once[dr], [&]() {
+    attr_status[dr] = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+  });
+  if (attr_status[dr] != hipSuccess) return attr_status[dr];
   int per_cu = int((160 * 1024) / (lds_bytes + 512));
   per_cu = per_cu < 1 ? 1 : per_cu > 4 ? 4 : per_cu;
   int64_t grid = int64_t(smallc_num_cus()) * per_cu;

@@ -18,7 +18,7 @@ no biases: the stack exercises the operators the paper defines, with the layer s
 
 from __future__ import annotations
 
-from typing import Dict, List, Tuple
+from typing import Callable, Dict, List, Tuple
 
 import torch
 
@@ -61,6 +61,7 @@ class ResNet18Stack:
         self.ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=self.dev)   # shared by the projections
         self._alloc("avg", (batch, 512))
         self.logits = torch.empty((batch, self.w["fc"].shape[0]), dtype=torch.float32, device=self.dev)
+        self.steps = self.plan()
 
     def _pack(self, name: str, x_shape: Tuple[int, ...], s: int, p: int) -> torch.Tensor:
         need = gs.conv2d_workspace(self.x, self.w[name], (s, s), (p, p), x_shape=x_shape)
@@ -87,17 +88,35 @@ class ResNet18Stack:
         """Names of the library calls of one forward pass, in order."""
         return ["conv1", "pool"] + [n for n in self.spec if n != "conv1"] + ["avg", "fc"]
 
-    def forward(self, x: torch.Tensor = None) -> torch.Tensor:
-        if x is not None:
-            self.x.copy_(x)
-        y = self._conv("conv1", self.x)
-        y = gs.windows_reduce(y, 2, (3, 3), (2, 2), (1, 1), (1, 1), gs.GS_MAX, out=self.bufs["pool"])
+    def plan(self) -> List[Tuple[str, Callable[[], torch.Tensor]]]:
+        """The forward pass as (layer name, call) pairs in execution order.  Every call reads and
+        writes this object's fixed buffers, so a call can be launched (and timed) on its own once
+        the calls before it have run."""
+        b = self.bufs
+        steps: List[Tuple[str, Callable[[], torch.Tensor]]] = [
+            ("conv1", lambda: self._conv("conv1", self.x)),
+            ("pool", lambda: gs.windows_reduce(b["conv1"], 2, (3, 3), (2, 2), (1, 1), (1, 1), gs.GS_MAX, out=b["pool"])),
+        ]
+        y = "pool"
         for stage in (1, 2, 3, 4):
             for block in (1, 2):
                 pre = f"s{stage}b{block}"
-                t = self._conv(pre + "c1", y)
-                shortcut = self._conv(pre + "proj", y, relu=False) if (pre + "proj") in self.spec else y
-                y = self._conv(pre + "c2", t, residual=shortcut)
-        hw = y.shape[-1] * y.shape[-2]
-        avg = gs.reduce(y, 2, gs.GS_SUM, scale=1.0 / hw, out=self.bufs["avg"])
-        return gs.cartesian_dot(avg, self.w["fc"], out=self.logits)
+                steps.append((pre + "c1", lambda pre=pre, y=y: self._conv(pre + "c1", b[y])))
+                shortcut = y
+                if (pre + "proj") in self.spec:
+                    steps.append((pre + "proj", lambda pre=pre, y=y: self._conv(pre + "proj", b[y], relu=False)))
+                    shortcut = pre + "proj"
+                steps.append((pre + "c2", lambda pre=pre, sc=shortcut: self._conv(pre + "c2", b[pre + "c1"], residual=b[sc])))
+                y = pre + "c2"
+        hw = b[y].shape[-1] * b[y].shape[-2]
+        steps.append(("avg", lambda y=y: gs.reduce(b[y], 2, gs.GS_SUM, scale=1.0 / hw, out=b["avg"])))
+        steps.append(("fc", lambda: gs.cartesian_dot(b["avg"], self.w["fc"], out=self.logits)))
+        return steps
+
+    def forward(self, x: torch.Tensor = None) -> torch.Tensor:
+        if x is not None:
+            self.x.copy_(x)
+        out = None
+        for _name, call in self.steps:
+            out = call()
+        return out

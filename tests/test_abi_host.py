@@ -32,7 +32,8 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(gs.EXPORTS)
     lib = gs.lib()
     for name in declared:
-        assert getattr(lib, name) is not None
+        # without declared argument types ctypes would pass pointers (streams, workspaces) as 32-bit ints
+        assert getattr(lib, name).argtypes is not None, name
 
 
 def test_status_strings():
