@@ -44,20 +44,25 @@ KERNEL_SOURCES = {
     "reduce": ("reduce.hip", "common.h"),
     "move": ("move.hip", "common.h"),
     "gemm": ("gemm.hip", "common.h"),
+    "depthwise": ("depthwise.hip", "common.h"),
 }
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (27.06e6 + 25.70e6, "conv", "4ebf63857bc68278605d03281a72280ddce866b7d4199408f60a0a8f11eff7e3"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
-    "conv3x3": (14.21e6 + 12.85e6, "conv", "4ebf63857bc68278605d03281a72280ddce866b7d4199408f60a0a8f11eff7e3"),
-    "conv3x3_b64": (27.06e6 + 25.70e6, "conv", "4ebf63857bc68278605d03281a72280ddce866b7d4199408f60a0a8f11eff7e3"),
-    "im2col_gather": (12.97e6 + 115.65e6, "windows", "8f213e3d6e591679d90f6e8ac8b07596ca76345f9b6d3594b7300899d3b80672"),
-    "maxpool": (102.99e6 + 25.69e6, "reduce", "9eb204f97458193b5ff9a1e28624d7ce9aa9d701c334204564151583e275147e"),
-    "reduce": (268.44e6 + 0.52e6, "reduce", "9eb204f97458193b5ff9a1e28624d7ce9aa9d701c334204564151583e275147e"),
-    "transpose": (25.76e6 + 25.70e6, "move", "51ea9bb799d81af55674aeeb70557e247c1f0d9205b92f83666c6b67f5baa81f"),
-    "dense_blocked": (64 * (5.65e6 + 1.05e6), "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),       # 64 launches per step, each of one 512^3 block
-    "dense": (1635.93e6 + 274.91e6, "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),
-    "mlp_scaled": (29.33e6 + 16.78e6, "gemm", "318564be9306f0e062996f444ffc920da584028a54367fd075d4e6f4fcf3f19e"),
+    "resnet18": (27.02e6 + 25.70e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
+    "conv3x3": (14.17e6 + 12.85e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),
+    "conv3x3_b64": (27.02e6 + 25.70e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),
+    "im2col_gather": (12.97e6 + 115.65e6, "windows", "73f116a0bb80087b6af37968efdb14e1a0517e45a6da7cef5f805b3f09ab057e"),
+    "maxpool": (103.00e6 + 25.69e6, "reduce", "180c36ab7b85e7e66d63ff7564b1c7bd24a526549346ed6a9b74759668152a28"),
+    "reduce": (268.44e6 + 0.52e6, "reduce", "180c36ab7b85e7e66d63ff7564b1c7bd24a526549346ed6a9b74759668152a28"),
+    "transpose": (25.76e6 + 25.70e6, "move", "e096a90e3193bc6a6d23d573507162820f4a64b388070ede784ca88b292a8910"),
+    "dense_blocked": (64 * (5.66e6 + 1.05e6), "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),       # 64 launches per step, each of one 512^3 block
+    "dense": (1611.42e6 + 279.13e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
+    "mlp_scaled": (28.86e6 + 16.78e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
+    "conv3x3_i8": (7.28e6 + 25.71e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),
+    "dense_i8": (805.87e6 + 284.22e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
+    "dense_fp8": (806.17e6 + 134.22e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
+    "depthwise": (103.03e6 + 102.76e6, "depthwise", "edb2db01b3d395c6096b07f9139c787304765e7b85dbc17534b1ddb8d4f2adaf"),
 }
 
 
