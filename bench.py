@@ -551,15 +551,16 @@ class DenseFp8(DenseBig):
 
 
 class DenseBlocked(_Simple):
-    """The blocked form of the product (slice / dotProd / pair + reduceSum / concat, one launch per
-    block and K slice) on 2048 x 2048 x 2048 bf16 with cubic blocks of TILE: the tile-shape sweep
-    of the paper's systolic-array sizes.  TILE = 2048 is the unblocked product."""
+    """The blocked form of the product (slice / dotProd / pair + reduceSum / concat) on
+    2048 x 2048 x 2048 bf16 with cubic blocks of TILE, one launch whose workgroups stay inside
+    blocks and fold the K slices in order: the tile-shape sweep of the paper's systolic-array
+    sizes.  TILE = 2048 is the unblocked product."""
 
     TILE = 512
-    dominant = "gemm_nt_* (one launch per block and K slice)"
+    dominant = "gemm_nt_dma_kernel (tiles confined to blocks)"
     bound, unit, peak = "mfma", "TFLOP/s", PEAK_BF16_TFLOPS
     name = property(lambda self: f"cartesian_dot_blocked 2048^3 bf16 -> f32, blocks of {self.TILE}^3 "
-                                 f"({(2048 // self.TILE) ** 3} launches per step)")
+                                 f"({(2048 // self.TILE) ** 3} block products per step, one launch)")
 
     def __init__(self, dev):
         from paper_2105_09377_amd import binding as gs, synth
@@ -654,7 +655,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="resnet18", choices=sorted(WORKLOADS))
     ap.add_argument("--tile", type=int, default=None,
-                    help="dense_blocked only: edge of the cubic blocks (a divisor of 2048, at least 128; default 512)")
+                    help="dense_blocked only: edge of the cubic blocks (a divisor of 2048, at least 64; default 512)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batches", type=int, default=5,
                     help="timed batches of --steps steps each; the reported time is the median batch")
@@ -682,8 +683,8 @@ def main():
                                              "write_bytes": dst.numel() * 4}}))
         return
     if args.tile is not None:
-        if args.workload != "dense_blocked" or args.tile < 128 or 2048 % args.tile:
-            sys.exit("--tile needs --workload dense_blocked and a divisor of 2048 that is at least 128")
+        if args.workload != "dense_blocked" or args.tile < 64 or 2048 % args.tile:
+            sys.exit("--tile needs --workload dense_blocked and a divisor of 2048 that is at least 64")
         DenseBlocked.TILE = args.tile
     wl = WORKLOADS[args.workload](dev)
     stream = torch.cuda.Stream(device=dev)

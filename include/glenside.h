@@ -97,13 +97,16 @@ int glenside_cartesian_dot(const gs_ap* a0, const gs_ap* a1, gs_ap* out, int act
 
 /* The blocked form of the same product (Sec. 5.4; the rewrites of Fig. 6 applied as in Fig. 7):
  * a0 ((M),(K)), a1 ((N),(K)), out ((M,N),()) of the accumulator's type (GS_I32 for int8 inputs,
- * GS_F32 for bfloat16).  The result is the concat, along both access dimensions, of blocks of at
- * most tile_m x tile_n results; each block is the left-to-right fold, by reduceSum (pair acc part),
- * of dotProd over slices of at most tile_k compute elements -- one contraction launch per
- * (block, K slice) on views of the operands, nothing is copied.  Equal to glenside_cartesian_dot
- * exactly for integers and up to the summation order for floats.  More than 65536 launches are
- * refused with GS_ERR_UNSUPPORTED.  This is the tile-shape sweep of the paper's "systolic array"
- * sizes; the unblocked entry point is the fast path.                                              */
+ * GS_F32 for bfloat16 and 8-bit floats).  The result is the concat, along both access dimensions,
+ * of blocks of at most tile_m x tile_n results; each block is the left-to-right fold, by
+ * reduceSum (pair acc part), of dotProd over slices of at most tile_k compute elements.
+ * When the slices are whole 128-byte runs of K (tile_k * element size a multiple of 128) or there
+ * is a single slice, this is ONE launch: no workgroup's tile crosses a block boundary and each
+ * walks its block's slices in order, folding them in its accumulators.  Other slice lengths take
+ * one contraction launch per (block, K slice) on views of the operands (nothing is copied; more
+ * than 65536 launches are refused with GS_ERR_UNSUPPORTED).  Equal to glenside_cartesian_dot
+ * exactly for integers and up to the summation order for floats.  This is the tile-shape sweep of
+ * the paper's "systolic array" sizes.                                                            */
 int glenside_cartesian_dot_blocked(const gs_ap* a0, const gs_ap* a1, int64_t tile_m, int64_t tile_n,
                                    int64_t tile_k, gs_ap* out, void* stream);
 

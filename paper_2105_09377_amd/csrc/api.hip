@@ -290,9 +290,31 @@ int glenside_cartesian_dot_blocked(const gs_ap* a0, const gs_ap* a1, int64_t til
   }
   const int64_t M = a0->shape[0], N = a1->shape[0], K = a0->shape[1];
   if (M == 0 || N == 0) return GS_OK;
+  const size_t esz = dtype_size(a0->dtype);
+  // K slices that are whole 128-byte slabs of the contraction kernels (or a single slice): ONE
+  // launch.  The result is cut into tile_m x tile_n blocks, every workgroup's tile lies inside one
+  // block and walks that block's K slices in order, folding them in its accumulators (the
+  // reduceSum (pair acc part) chain of Fig. 7, left to right).
+  if (tile_k >= K || (tile_k * int64_t(esz)) % 128 == 0) {
+    GemmArgs g{};
+    memset(&g, 0, sizeof(g));
+    g.x = a0->data;
+    g.y = a1->data;
+    g.out = out->data;
+    g.in_dtype = a0->dtype;
+    g.out_dtype = out->dtype;
+    g.I = M;
+    g.J = N;
+    g.K = K;
+    g.ldx = g.ldy = K;
+    g.jp = N;
+    g.bm = tile_m < M ? tile_m : 0;
+    g.bn = tile_n < N ? tile_n : 0;
+    return launch_status(launch_gemm(g, static_cast<hipStream_t>(stream)));
+  }
+  // Other slice lengths: one launch per (block, K slice) on views of the operands.
   const int64_t launches = ceil_div(M, tile_m) * ceil_div(N, tile_n) * (K > 0 ? ceil_div(K, tile_k) : 1);
   if (launches > 65536) return GS_ERR_UNSUPPORTED;
-  const size_t esz = dtype_size(a0->dtype);
   for (int64_t m0 = 0; m0 < M; m0 += tile_m)
     for (int64_t n0 = 0; n0 < N; n0 += tile_n) {
       // dotProd over (slice a0 [m0,m1) x [k0,k1)) x (slice a1 [n0,n1) x [k0,k1)); the K blocks are

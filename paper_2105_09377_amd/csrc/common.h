@@ -258,6 +258,10 @@ struct GemmArgs {         // C[i][j] = sum_k X[i][k] * Y[j][k]
   int64_t jp;             // out element offset = (j / jp) * (I * jp) + i * jp + (j % jp)
   int relu;
   int vj;                 // set by launch_gemm: columns per lane of the vector write-back (1 = scalar)
+  // Blocked evaluation (0 = off): the result is cut into blocks of bm x bn and no tile of a
+  // kernel straddles a block boundary -- a workgroup's tile lies inside one block, whose K range
+  // it walks from the first slice to the last.
+  int64_t bm, bn;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 

@@ -55,6 +55,40 @@ __device__ inline void tile_of_block(int64_t bid, int64_t nblocks, int64_t tiles
   *tj = r / rows_here;
 }
 
+// The rows [i0, ilim) and columns [j0, jlim) a tile may touch.  Unblocked: tile (ti, tj) starts at
+// (ti * BM, tj * BN) and ends with the matrix.  Blocked: tiles are counted block by block
+// (ceil(bm / BM) tile rows per block row) and end with their block; a tile past the end of a
+// smaller last block is empty.
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(v)));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(v) >> 32));
+  return int64_t((uint64_t(hi) << 32) | lo);
+}
+struct TileBox {
+  int64_t i0, j0, ilim, jlim;
+};
+__host__ __device__ inline int64_t tile_count(int64_t extent, int64_t block, int tile) {
+  return block > 0 ? ceil_div(extent, block) * ceil_div(block, tile) : ceil_div(extent, tile);
+}
+__device__ inline void tile_span(int64_t t, int64_t extent, int64_t block, int tile, int64_t* lo, int64_t* lim) {
+  if (block <= 0) {
+    *lo = t * tile;
+    *lim = extent;
+    return;
+  }
+  const int64_t per = ceil_div(block, tile), b = t / per;
+  *lo = b * block + (t - b * per) * tile;
+  const int64_t end = (b + 1) * block;
+  *lim = end < extent ? end : extent;
+}
+template <int BM, int BN>
+__device__ inline TileBox tile_box(const GemmArgs& a, int64_t ti, int64_t tj) {
+  TileBox b;
+  tile_span(ti, a.I, a.bm, BM, &b.i0, &b.ilim);
+  tile_span(tj, a.J, a.bn, BN, &b.j0, &b.jlim);
+  return b;
+}
+
 // General (checked) load of one 16-byte chunk: zero beyond the row's K bytes, byte loads when the
 // rows are not 16-byte aligned.  Used by the edge/unaligned kernel only.
 template <bool VEC>
@@ -84,8 +118,10 @@ __global__ void __launch_bounds__(256) gemm_nt_checked_kernel(GemmArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t tiles_j = ceil_div(a.J, BN);
-  const int64_t i0 = (blockIdx.x / tiles_j) * BM, j0 = (blockIdx.x % tiles_j) * BN;
+  const int64_t tiles_j = tile_count(a.J, a.bn, BN);
+  const TileBox box = tile_box<BM, BN>(a, blockIdx.x / tiles_j, blockIdx.x % tiles_j);
+  const int64_t i0 = box.i0, j0 = box.j0;
+  if (i0 >= box.ilim || j0 >= box.jlim) return;          // past the end of a smaller last block
   const int64_t Kb = a.K * TR::kEsz;
   const uint8_t* X = static_cast<const uint8_t*>(a.x);
   const uint8_t* Y = static_cast<const uint8_t*>(a.y);
@@ -102,12 +138,12 @@ __global__ void __launch_bounds__(256) gemm_nt_checked_kernel(GemmArgs a) {
 #pragma unroll
     for (int r = 0; r < XCH; ++r) {
       const int c = tid + 256 * r, row = c >> 3, kc = c & 7;
-      xr[r] = load_chunk_checked<VEC>(X + (i0 + row) * ldxb, k0 + kc * 16, Kb, i0 + row < a.I);
+      xr[r] = load_chunk_checked<VEC>(X + (i0 + row) * ldxb, k0 + kc * 16, Kb, i0 + row < box.ilim);
     }
 #pragma unroll
     for (int r = 0; r < YCH; ++r) {
       const int c = tid + 256 * r, row = c >> 3, kc = c & 7;
-      yr[r] = load_chunk_checked<VEC>(Y + (j0 + row) * ldyb, k0 + kc * 16, Kb, j0 + row < a.J);
+      yr[r] = load_chunk_checked<VEC>(Y + (j0 + row) * ldyb, k0 + kc * 16, Kb, j0 + row < box.jlim);
     }
   };
   auto store_slab = [&](int buf) {
@@ -149,12 +185,12 @@ __global__ void __launch_bounds__(256) gemm_nt_checked_kernel(GemmArgs a) {
   }
 
   const int64_t j = j0 + wn * 32 + (lane & 31);
-  if (j < a.J) {
+  if (j < box.jlim) {
     const int64_t jbase = (j / a.jp) * (a.I * a.jp) + (j % a.jp);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int64_t i = i0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      if (i < a.I)
+      if (i < box.ilim)
         store_result<typename TR::acc_t>(a.out, a.residual, a.out_dtype, jbase + i * a.jp, acc[v],
                                          a.relu);
     }
@@ -187,10 +223,13 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int64_t tiles_i = ceil_div(a.I, BM), tiles_j = ceil_div(a.J, BN);
+  const int64_t tiles_i = tile_count(a.I, a.bm, BM), tiles_j = tile_count(a.J, a.bn, BN);
   int64_t ti, tj;
   tile_of_block(blockIdx.x, gridDim.x, tiles_i, tiles_j, &ti, &tj);
-  const int64_t i0 = ti * BM, j0 = tj * BN;
+  const TileBox box = tile_box<BM, BN>(a, ti, tj);
+  // the tile origin is the same for every lane: say so, the transfers take their base in scalar registers
+  const int64_t i0 = uniform64(box.i0), j0 = uniform64(box.j0);
+  if (i0 >= box.ilim || j0 >= box.jlim) return;          // past the end of a smaller last block
 
   const uint8_t* X = static_cast<const uint8_t*>(a.x);
   const uint8_t* Y = static_cast<const uint8_t*>(a.y);
@@ -219,13 +258,13 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
 #pragma unroll
   for (int q = 0; q < XQ; ++q) {
     int64_t row = (wave + q * NW) * RPI + lrow;
-    row = i0 + row < a.I ? row : a.I - 1 - i0;
+    row = i0 + row < box.ilim ? row : box.ilim - 1 - i0;
     xoff[q] = uint32_t(row * ldxb + lcol);
   }
 #pragma unroll
   for (int q = 0; q < YQ; ++q) {
     int64_t row = (wave + q * NW) * RPI + lrow;
-    row = j0 + row < a.J ? row : a.J - 1 - j0;
+    row = j0 + row < box.jlim ? row : box.jlim - 1 - j0;
     yoff[q] = uint32_t(row * ldyb + lcol);
   }
   // In a short last slab the 16-byte columns past K are not multiplied; their lanes re-read
@@ -396,7 +435,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
       constexpr int LPR = WN / VJ, RPP = 64 / LPR, NP = 32 / RPP;   // lanes per row, rows per pass, passes
       const int cq = lane % LPR, rsub = lane / LPR;
       const int64_t jg = j0 + wn * WN + cq * VJ;
-      const bool j_ok = jg < a.J;
+      const bool j_ok = jg < box.jlim;
       const int64_t jq = j_ok ? jg : 0;
       const int64_t jbase = (jq / a.jp) * (a.I * a.jp) + (jq % a.jp);
       static_for<MI>([&](auto m_) {
@@ -418,7 +457,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
           const int64_t i = i0 + wm * WM + m * 32 + p * RPP + rsub;
-          const bool ok = j_ok && i < a.I;
+          const bool ok = j_ok && i < box.ilim;
           const int64_t addr = ok ? jbase + i * a.jp : 0;
           if constexpr (kind == 2) {
             float f[VJ];
@@ -505,7 +544,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
   static_for<NJ>([&](auto n_) {
     constexpr int n = decltype(n_)::value;
     const int64_t j = j0 + wn * WN + n * 32 + (lane & 31);
-    const bool j_ok = j < a.J;
+    const bool j_ok = j < box.jlim;
     const int64_t jbase = (j / a.jp) * (a.I * a.jp) + (j % a.jp);
     static_for<MI>([&](auto m_) {
       constexpr int m = decltype(m_)::value;
@@ -513,7 +552,7 @@ __global__ void __launch_bounds__(WGM * WGN * 64) gemm_nt_dma_kernel(GemmArgs a)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int64_t i = ibase + 8 * (v >> 2) + (v & 3);
-        if (j_ok && i < a.I)
+        if (j_ok && i < box.ilim)
           store_result<typename TR::acc_t>(a.out, a.residual, a.out_dtype, jbase + i * a.jp,
                                            acc[m][n][v], a.relu, stream_out);
       }
@@ -533,7 +572,8 @@ static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
   });
   if (attr_status != hipSuccess) return attr_status;
-  const int64_t tiles = ceil_div(a.I, BM) * ceil_div(a.J, BN);
+  const int64_t tiles = tile_count(a.I, a.bm, BM) * tile_count(a.J, a.bn, BN);
+  if (tiles > 0x7fffffff) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3(unsigned(tiles)), dim3(WGM * WGN * 64), lds_bytes, s, a);
   return hipGetLastError();
 }
@@ -541,12 +581,14 @@ static hipError_t launch_dma(const GemmArgs& a, hipStream_t s) {
 // Tile choice of the direct-to-LDS kernel.
 template <typename TR>
 static hipError_t launch_dma_tiles(const GemmArgs& a, hipStream_t s) {
-  const int64_t t128 = ceil_div(a.I, 128) * ceil_div(a.J, 128);
-  const int64_t t256 = ceil_div(a.I, 256) * ceil_div(a.J, 256);
-  if (t256 >= 256 && a.I >= 256 && a.J >= 256) return launch_dma<TR, 256, 256, 2, 4, 128, 2>(a, s);
+  const int64_t t128 = tile_count(a.I, a.bm, 128) * tile_count(a.J, a.bn, 128);
+  const int64_t t256 = tile_count(a.I, a.bm, 256) * tile_count(a.J, a.bn, 256);
+  // extent a tile can fill: the block when the result is cut into blocks
+  const int64_t fi = a.bm > 0 && a.bm < a.I ? a.bm : a.I, fj = a.bn > 0 && a.bn < a.J ? a.bn : a.J;
+  if (t256 >= 256 && fi >= 256 && fj >= 256) return launch_dma<TR, 256, 256, 2, 4, 128, 2>(a, s);
   // few rows (a convolution's output channels against many positions): tiles 64 rows tall
-  if (a.I <= 64 && ceil_div(a.J, 256) >= 192) return launch_dma<TR, 64, 256, 1, 4, 128, 2>(a, s);
-  if (t128 >= 192) return launch_dma<TR, 128, 128, 2, 2, 128, 2>(a, s);
+  if (a.I <= 64 && ceil_div(fj, 256) * ceil_div(a.J, fj) >= 192) return launch_dma<TR, 64, 256, 1, 4, 128, 2>(a, s);
+  if (t128 >= 192 && (a.bm <= 0 || fi >= 128) && (a.bn <= 0 || fj >= 128)) return launch_dma<TR, 128, 128, 2, 2, 128, 2>(a, s);
   return launch_dma<TR, 64, 64, 2, 2, 128, 2>(a, s);
 }
 
@@ -566,13 +608,14 @@ static hipError_t launch_t(const GemmArgs& a, hipStream_t s) {
     const size_t osz = dtype_size(a.out_dtype);
     for (int cand = 8; cand >= 4 && v.vj == 1; cand /= 2) {
       const size_t al = cand * osz < 16 ? cand * osz : 16;
-      if (a.jp % cand == 0 && a.J % cand == 0 && reinterpret_cast<uintptr_t>(a.out) % al == 0 &&
+      if (a.jp % cand == 0 && a.J % cand == 0 && a.bn % cand == 0 && reinterpret_cast<uintptr_t>(a.out) % al == 0 &&
           reinterpret_cast<uintptr_t>(a.residual) % al == 0)
         v.vj = cand;
     }
     return launch_dma_tiles<TR>(v, s);
   }
-  const int64_t tiles = ceil_div(a.I, 64) * ceil_div(a.J, 64);
+  const int64_t tiles = tile_count(a.I, a.bm, 64) * tile_count(a.J, a.bn, 64);
+  if (tiles > 0x7fffffff) return hipErrorInvalidValue;
   if (vec)
     hipLaunchKernelGGL((gemm_nt_checked_kernel<TR, true>), dim3(unsigned(tiles)), dim3(256), 0, s, a);
   else
