@@ -3,6 +3,7 @@
 the library's fixed scratch array."""
 
 import ctypes
+import gc
 
 import pytest
 import torch
@@ -18,10 +19,11 @@ def _both(cfg, odt, residual=None, act=gs.GS_ACT_NONE):
     res = None if residual is None else residual.to(DEV)
     want = gs.conv2d_direct(x, w, cfg["stride"], cfg["pad"], residual=res, act=act, out_dtype=odt)
     out = torch.empty_like(want)
+    gc.collect()                                            # tensors of earlier tests go now, not during the call
     torch.cuda.synchronize()
     before = torch.cuda.memory_allocated()
     got = gs.conv2d_direct_static(x, w, cfg["stride"], cfg["pad"], residual=res, act=act, out=out)
-    assert torch.cuda.memory_allocated() == before          # torch allocated nothing for the call
+    assert torch.cuda.memory_allocated() <= before          # torch allocated nothing for the call
     torch.cuda.synchronize()
     assert got.data_ptr() == out.data_ptr()
     return got, want
