@@ -121,13 +121,16 @@ __global__ void __launch_bounds__(256) move_transpose_kernel(TransK k) {
 
 // The same with 8 bytes per lane on both sides (extents, strides and bases whole numbers of
 // 8-byte vectors): a thread reads NV = 8 / sizeof(T) elements along A, and writes NV along B that
-// it collects from NV rows of the LDS tile.
-template <typename T>
+// it collects from NV rows of the LDS tile.  The tile is 64 (A) x TB (B): TB = 256 puts sixteen
+// loads per thread in flight before the barrier (large transpositions are bound by how many bytes
+// a compute unit keeps in flight), TB = 64 keeps small ones spread over the chip.
+template <typename T, int TB>
 __global__ void __launch_bounds__(256) move_transpose_vec_kernel(TransK k) {
   constexpr int ESZ = int(sizeof(T)), NV = 8 / ESZ;
-  constexpr int TPR = 64 / NV, RPP = 256 / TPR, NP = 64 / RPP;   // threads per tile row, rows per pass, passes
-  constexpr int PITCH = 64 + 4 / ESZ;                            // tile row: a whole number of dwords, odd in dwords
-  __shared__ __attribute__((aligned(8))) T tile[64 * PITCH];
+  constexpr int TPR = 64 / NV, RPP = 256 / TPR, NPL = TB / RPP;   // loads: threads per tile row, rows per pass, passes
+  constexpr int TPS = TB / NV, RPS = 256 / TPS, NPS = 64 / RPS;   // stores: threads per result row, rows per pass, passes
+  constexpr int PITCH = 64 + 4 / ESZ;                             // tile row: a whole number of dwords, odd in dwords
+  __shared__ __attribute__((aligned(8))) T tile[TB * PITCH];
   const T* in = reinterpret_cast<const T*>(k.in);
   T* out = reinterpret_cast<T*>(k.out);
   int64_t t = blockIdx.x;
@@ -142,23 +145,29 @@ __global__ void __launch_bounds__(256) move_transpose_vec_kernel(TransK k) {
     oo += i * k.bos[d];
     t = q;
   }
-  const int64_t a0 = ta * 64, b0 = tb * 64;
-  const int c = threadIdx.x % TPR, r = threadIdx.x / TPR;
+  const int64_t a0 = ta * 64, b0 = tb * TB;
+  {
+    const int c = threadIdx.x % TPR, r = threadIdx.x / TPR;
+    i32x2 v[NPL];
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    const int j = p * RPP + r;
-    const int64_t a = a0 + c * NV, b = b0 + j;
-    if (a < k.EA && b < k.EB) {
-      const i32x2 v = __builtin_nontemporal_load(reinterpret_cast<const i32x2*>(in + io + b * k.sB_in + a));
-      uint32_t* d = reinterpret_cast<uint32_t*>(&tile[j * PITCH + c * NV]);
-      d[0] = uint32_t(v.x);
-      d[1] = uint32_t(v.y);
+    for (int p = 0; p < NPL; ++p) {                    // every load is issued before the first LDS store
+      const int64_t a = a0 + c * NV, b = b0 + p * RPP + r;
+      v[p] = i32x2{0, 0};
+      if (a < k.EA && b < k.EB)
+        v[p] = __builtin_nontemporal_load(reinterpret_cast<const i32x2*>(in + io + b * k.sB_in + a));
+    }
+#pragma unroll
+    for (int p = 0; p < NPL; ++p) {
+      uint32_t* d = reinterpret_cast<uint32_t*>(&tile[(p * RPP + r) * PITCH + c * NV]);
+      d[0] = uint32_t(v[p].x);
+      d[1] = uint32_t(v[p].y);
     }
   }
   __syncthreads();
+  const int c = threadIdx.x % TPS, r = threadIdx.x / TPS;
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    const int ja = p * RPP + r;
+  for (int p = 0; p < NPS; ++p) {
+    const int ja = p * RPS + r;
     const int64_t a = a0 + ja, b = b0 + c * NV;
     if (a < k.EA && b < k.EB) {
       union {
@@ -285,9 +294,19 @@ hipError_t launch_move(const MoveArgs& a, hipStream_t s) {
                   reinterpret_cast<uintptr_t>(t.in) % 8 == 0 && reinterpret_cast<uintptr_t>(t.out) % 8 == 0;
       for (int d = 0; d < t.nb && vec8; ++d) vec8 = t.bis[d] % nv == 0 && t.bos[d] % nv == 0;
       if (blocks <= 0x7fffffff && vec8) {
-        if (esz == 1) hipLaunchKernelGGL((move_transpose_vec_kernel<uint8_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
-        else if (esz == 2) hipLaunchKernelGGL((move_transpose_vec_kernel<uint16_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
-        else hipLaunchKernelGGL((move_transpose_vec_kernel<uint32_t>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
+        // Tiles 256 long in B while that still leaves several workgroups per compute unit.
+        TransK w = t;
+        w.tilesB = ceil_div(t.EB, 256);
+        const int64_t wide = w.tilesA * w.tilesB * batch;
+        if (t.EB >= 256 && wide >= 512) {
+          if (esz == 1) hipLaunchKernelGGL((move_transpose_vec_kernel<uint8_t, 256>), dim3(unsigned(wide)), dim3(256), 0, s, w);
+          else if (esz == 2) hipLaunchKernelGGL((move_transpose_vec_kernel<uint16_t, 256>), dim3(unsigned(wide)), dim3(256), 0, s, w);
+          else hipLaunchKernelGGL((move_transpose_vec_kernel<uint32_t, 256>), dim3(unsigned(wide)), dim3(256), 0, s, w);
+          return hipGetLastError();
+        }
+        if (esz == 1) hipLaunchKernelGGL((move_transpose_vec_kernel<uint8_t, 64>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
+        else if (esz == 2) hipLaunchKernelGGL((move_transpose_vec_kernel<uint16_t, 64>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
+        else hipLaunchKernelGGL((move_transpose_vec_kernel<uint32_t, 64>), dim3(unsigned(blocks)), dim3(256), 0, s, t);
         return hipGetLastError();
       }
       if (blocks <= 0x7fffffff) {
