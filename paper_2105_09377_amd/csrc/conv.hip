@@ -275,6 +275,7 @@ static hipError_t launch_conv_t(const ConvArgs& a_in, hipStream_t s) {
   g.max_rows = 0;
   g.tps = 0;
   g.rb_shift = 0;
+  g.pos_major = 0;
   g.dHWo = FastDiv::make(uint32_t(g.HWo > 0 ? g.HWo : 1));
   g.dWo = FastDiv::make(uint32_t(a.Wo > 0 ? a.Wo : 1));
   if (g.M == 0 || a.O == 0) return hipSuccess;

@@ -93,7 +93,19 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   }
   g.max_rows = conv_max_rows(a, g.M, g.HWo, g.tps);
   if (g.max_rows < 0) return hipErrorInvalidValue;
-  g.dTiles = FastDiv::make(uint32_t(ceil_div(g.M, g.tps)));
+  // Tile order.  An XCD (private L2) owns a contiguous range of tiles.  Channel tile first: its
+  // workgroups share a channel tile's weights, and every channel tile re-reads the input.
+  // Position tile first: they share a patch, and every XCD reads all the weights -- once if they
+  // stay in its L2 (4 MB), else once per position tile.  Take the order that fetches less.
+  {
+    const double in_b = double(a.N) * a.C * a.H * a.W * TR::kEsz;
+    const double w_b = double(a.O) * a.C * a.Kh * a.Kw * TR::kEsz;
+    const int64_t n_ot = ceil_div(a.O, TO), tiles_m = ceil_div(g.M, g.tps);
+    const double ch_first = in_b * double(n_ot) + w_b * (n_ot < 8 ? 8.0 / double(n_ot) : 1.0);
+    const double pos_first = in_b + w_b * 8.0 * (w_b > 3.0e6 ? double(ceil_div(tiles_m, 8)) : 1.0);
+    g.pos_major = (n_ot > 1 && pos_first < ch_first) ? 1 : 0;
+    g.dTiles = FastDiv::make(uint32_t(g.pos_major ? n_ot : tiles_m));
+  }
   g.dW = FastDiv::make(uint32_t(a.W));
   g.dXG = FastDiv::make(1);
   // Patch row pitch: g.PW pixels of 48 bytes with g.PW * 3 / 2 odd, so that consecutive patch rows

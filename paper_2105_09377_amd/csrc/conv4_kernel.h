@@ -100,7 +100,8 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   // A work item ("tile" below) is (position tile, channel tile, K split): the split index runs
   // fastest so that workgroups launched together share a patch.
   const int ksplit = a.ksplit, kshift = ksplit == 4 ? 2 : ksplit == 2 ? 1 : 0;
-  const int n_tiles = tiles_m * ((a.O + TO - 1) / TO) * ksplit;
+  const int n_ot = (a.O + TO - 1) / TO;
+  const int n_tiles = tiles_m * n_ot * ksplit;
   const FastDiv dTiles = g.dTiles;
   const int Kh = KH ? KH : a.Kh, Kw = KW ? KW : a.Kw;
   const int T = Kh * Kw;
@@ -123,8 +124,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   };
   auto tile_range = [&](int item, int* m0, int* mend, int* o0) {
     const int tile = lg(item) >> kshift;
-    const int to = int(dTiles.div(uint32_t(tile)));
-    *m0 = (tile - to * tiles_m) * tps;
+    const int q = int(dTiles.div(uint32_t(tile)));
+    // channel tile first: tile = to * tiles_m + mt; position tile first: tile = mt * n_ot + to
+    const int to = g.pos_major ? tile - q * n_ot : q;
+    const int mt = g.pos_major ? q : tile - q * tiles_m;
+    *m0 = mt * tps;
     *o0 = to * TO;
     *mend = *m0 + tps < M ? *m0 + tps : M;
   };

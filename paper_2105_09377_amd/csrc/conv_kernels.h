@@ -38,8 +38,10 @@ struct ConvGeom {
   int pair_ok;      // W even: pixel pairs may be loaded with one access
   int tps;          // producer/consumer kernel: positions a tile covers (<= its MFMA width TP)
   int rb_shift;     // producer/consumer kernel: log2 of the patch rows per block of producer items
+  int pos_major;    // producer/consumer kernel: tiles numbered position tile first (all channel tiles of a
+                    // position tile are neighbours) instead of channel tile first
   FastDiv dHWo, dWo;  // division by Ho*Wo and by Wo
-  FastDiv dTiles, dXG, dW;   // producer/consumer kernel: by position tiles, pixel groups per row, W
+  FastDiv dTiles, dXG, dW;   // producer/consumer kernel: by position tiles (channel tiles if pos_major), pixel groups per row, W
 };
 
 struct SegTable {
