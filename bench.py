@@ -49,20 +49,20 @@ KERNEL_SOURCES = {
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (27.02e6 + 25.70e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
-    "conv3x3": (14.17e6 + 12.85e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),
-    "conv3x3_b64": (27.02e6 + 25.70e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),
-    "im2col_gather": (12.97e6 + 115.65e6, "windows", "73f116a0bb80087b6af37968efdb14e1a0517e45a6da7cef5f805b3f09ab057e"),
-    "maxpool": (103.00e6 + 25.69e6, "reduce", "180c36ab7b85e7e66d63ff7564b1c7bd24a526549346ed6a9b74759668152a28"),
-    "reduce": (268.44e6 + 0.52e6, "reduce", "180c36ab7b85e7e66d63ff7564b1c7bd24a526549346ed6a9b74759668152a28"),
-    "transpose": (25.76e6 + 25.70e6, "move", "e096a90e3193bc6a6d23d573507162820f4a64b388070ede784ca88b292a8910"),
-    "dense_blocked": (64 * (5.66e6 + 1.05e6), "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),       # 64 launches per step, each of one 512^3 block
-    "dense": (1611.42e6 + 279.13e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
-    "mlp_scaled": (28.86e6 + 16.78e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
-    "conv3x3_i8": (7.28e6 + 25.71e6, "conv", "86c20fd8f524097018b9758864dd48a614de8ca9f51ed6e7a8fb1dac4e46ae75"),
-    "dense_i8": (805.87e6 + 284.22e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
-    "dense_fp8": (806.17e6 + 134.22e6, "gemm", "71facf889323b68749b03d1f2b22414b71a68228df7ad35e1c23bef426313b68"),
-    "depthwise": (103.03e6 + 102.76e6, "depthwise", "edb2db01b3d395c6096b07f9139c787304765e7b85dbc17534b1ddb8d4f2adaf"),
+    "resnet18": (27.02e6 + 25.70e6, "conv", "943a69904f04711da3886bdfd0323452cc55aab8e2a9811c4fa6572a1cde8e97"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
+    "conv3x3": (14.18e6 + 12.85e6, "conv", "943a69904f04711da3886bdfd0323452cc55aab8e2a9811c4fa6572a1cde8e97"),
+    "conv3x3_b64": (27.02e6 + 25.70e6, "conv", "943a69904f04711da3886bdfd0323452cc55aab8e2a9811c4fa6572a1cde8e97"),
+    "im2col_gather": (12.97e6 + 115.65e6, "windows", "7741b56696f4637c8ca3c5a547f3f4d48b8d1f212974cd69d7997399800e3506"),
+    "maxpool": (103.00e6 + 25.69e6, "reduce", "4b5f1c3525283bcdbdfedb76eecfe0a01ed922a83e0882400e3fedff4fb6d82c"),
+    "reduce": (268.44e6 + 0.52e6, "reduce", "4b5f1c3525283bcdbdfedb76eecfe0a01ed922a83e0882400e3fedff4fb6d82c"),
+    "transpose": (25.82e6 + 25.70e6, "move", "40b347065cd533b906745648d7a7fedda1c39a942e4e6c78a902680868b0b3b9"),
+    "dense_blocked": (50.63e6 + 16.78e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
+    "dense": (1611.42e6 + 281.85e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
+    "mlp_scaled": (28.91e6 + 16.78e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
+    "conv3x3_i8": (7.29e6 + 25.71e6, "conv", "943a69904f04711da3886bdfd0323452cc55aab8e2a9811c4fa6572a1cde8e97"),
+    "dense_i8": (805.93e6 + 287.46e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
+    "dense_fp8": (806.21e6 + 134.22e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
+    "depthwise": (103.03e6 + 102.76e6, "depthwise", "b55bbabacf3938893acb7ff9df30d54119d03cc82754824aaf4170d2facde200"),
 }
 
 
