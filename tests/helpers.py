@@ -59,8 +59,9 @@ def assert_parity(got_t: torch.Tensor, ref: np.ndarray, float_tol: float = 1e-2,
     """Bit-exact for integer outputs; max relative error <= float_tol for float outputs (after an
     optional per-element absolute allowance `slack`, see fp8_slack)."""
     got = to_oracle(got_t)
-    want = expected_storage(ref, got_t.dtype)
+    want = expected_storage(np.asarray(ref), got_t.dtype).reshape(np.shape(ref))
     assert got.shape == want.shape, (what, got.shape, want.shape)
+    got, want = np.atleast_1d(got), np.atleast_1d(want)           # results with no dimensions at all
     if got_t.dtype in (torch.int8, torch.int32):
         bad = np.nonzero(got != want)
         assert bad[0].size == 0, f"{what}: {bad[0].size} integer mismatches, first at {[b[0] for b in bad]}"

@@ -112,3 +112,43 @@ def test_unsupported_and_workspace_errors():
         gs.program_eval("(compute dotProd (cartProd (access a 1) (slice (access a 1) 1 0 16)))", {"a": a}, out=out,
                         workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
     assert e.value.status == gs.GS_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+def test_random_programs(dtype):
+    """Two hundred seeded random programs (Table 1 transformers, dotProd / reduceSum / reduceMax) on small
+    tensors: whatever the library accepts must equal the oracle -- bit for bit on int8 inputs -- and it must
+    accept most of them; what it refuses, it must refuse with a status, launching nothing."""
+    import random_programs
+    rng = np.random.default_rng(20210509 + (0 if dtype == "i8" else 1))
+    shapes = {"a": (3, 4, 6, 5), "b": (6, 8), "c": (2, 1, 7)}
+    def make(shape, stream):
+        return synth.uniform_int8(shape, -5, 5, stream) if dtype == "i8" else synth.normal_bf16(shape, 1.0, stream)
+    tensors = {k: make(s, 9900 + i) for i, (k, s) in enumerate(shapes.items())}
+    tensors.update({k + "2": make(s, 9950 + i) for i, (k, s) in enumerate(shapes.items())})
+    same = {k: (k[:-1] if k.endswith("2") else k + "2") for k in tensors}
+    host = {k: to_oracle(v) for k, v in tensors.items()}
+    dev = {k: v.to(DEV) for k, v in tensors.items()}
+    ran = refused = 0
+    for i in range(200):
+        text = random_programs.grow(rng, host, same, depth=int(rng.integers(1, 6)))
+        want = sexpr.evaluate(text, host)
+        try:
+            got = gs.program_eval(text, dev)
+        except gs.GlensideError as e:
+            # rank: a cartProd inside a dotProd may exceed the eight dimensions of the boundary
+            assert e.status in (gs.GS_ERR_UNSUPPORTED, gs.GS_ERR_DTYPE) or \
+                (e.status == gs.GS_ERR_RANK and "cartProd" in text), (text, e.status)
+            refused += 1
+            continue
+        ran += 1
+        assert tuple(got.shape) == want.shape, text
+        ref = want.materialize()
+        if not np.isfinite(ref.astype(np.float64)).all():        # reduceMax over a padded window of -inf etc.
+            np.testing.assert_array_equal(np.isfinite(to_oracle(got)), np.isfinite(ref), err_msg=text)
+            continue
+        # a chain of computes stores its intermediate results in bfloat16 (one more rounding of
+        # 2^-9 per link, which a later cancellation can amplify); the oracle keeps fp64 throughout
+        chained = dtype == "bf16" and text.count("compute") > 1
+        assert_parity(got, ref, float_tol=5e-2 if chained else 1e-2, what=text)
+    assert ran >= 150, (ran, refused)
