@@ -176,3 +176,33 @@ def test_rewrite_refuses_programs_without_the_pattern():
     assert e.value.status == gs.GS_ERR_UNSUPPORTED
     with pytest.raises(gs.GlensideError):
         gs.program_rewrite(listings.MATMUL, "unknown-strategy", meta(activations=A[0, 0], weights=A[0, 0].T.copy()))
+
+
+def test_rewrites_on_random_shapes():
+    """Seeded sweep: random matrix sizes and block sizes (ragged last blocks, blocks larger than the
+    matrix, blocks of one), random convolution shapes and strides -- the rewritten program always
+    denotes the tensor the original does."""
+    r = rng(59)
+    for _ in range(25):
+        m_, n_, k_ = (int(v) for v in r.integers(1, 40, 3))
+        blocks = tuple(int(v) for v in r.integers(1, 48, 3))
+        P, Q = r.integers(-9, 9, (m_, k_)), r.integers(-9, 9, (k_, n_))
+        tensors = {"activations": P, "weights": Q}
+        if -(-m_ // blocks[0]) * -(-n_ // blocks[1]) * -(-k_ // blocks[2]) > 400:
+            continue
+        text = gs.program_rewrite(listings.MATMUL, "block", meta(**tensors), params=blocks)
+        np.testing.assert_array_equal(sexpr.evaluate(text, tensors).materialize(), P @ Q, err_msg=str((m_, n_, k_, blocks)))
+        sys_text = gs.program_rewrite("(compute dotProd (cartProd (access activations 1) (access (transpose (access weights 1) (list 1 0)) 1)))",
+                                      "systolic", meta(**tensors))
+        np.testing.assert_array_equal(sexpr.evaluate(sys_text, tensors).materialize(), P @ Q)
+    for _ in range(12):
+        n, c, o = (int(v) for v in r.integers(1, 4, 3))
+        kh, kw, sh, sw = (int(v) for v in r.integers(1, 4, 4))
+        h, w = int(r.integers(kh, kh + 7)), int(r.integers(kw, kw + 7))
+        A, W = r.integers(-8, 9, (n, c, h, w)), r.integers(-8, 9, (o, c, kh, kw))
+        ints = dict(C=c, Kh=kh, Kw=kw, Sh=sh, Sw=sw)
+        tensors = {"activations": A, "weights": W}
+        text = gs.program_rewrite(listings.CONV2D, "im2col", meta(**tensors), ints)
+        want = brute.conv2d(A, W, (sh, sw), (0, 0))
+        np.testing.assert_array_equal(sexpr.evaluate(text, tensors, ints).materialize(), want, err_msg=str(ints))
+        np.testing.assert_array_equal(sexpr.evaluate(listings.CONV2D, tensors, ints).materialize(), want)
