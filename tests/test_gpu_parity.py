@@ -290,6 +290,54 @@ def test_conv2d(case, form):
     assert_parity(got, conv_oracle(x, wt, stride, pad), what=f"{form} {case}")
 
 
+def _random_conv_cases(seed, count):
+    """Seeded shapes across the kernels' branches: channel counts on and off the 16 / 32 multiples,
+    widths that are and are not multiples of the producers' vectors, planes of 7..40, strides,
+    paddings up to half the window, rectangular windows, few and many output channels."""
+    r = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        dtype = ("bf16", "i8")[int(r.integers(2))]
+        n = int(r.integers(1, 6))
+        c = int(r.choice([3, 8, 16, 24, 32, 48, 64, 96, 128, 160, 256]))
+        h, w = int(r.integers(5, 41)), int(r.integers(5, 41))
+        o = int(r.choice([1, 5, 32, 64, 70, 128, 200, 256]))
+        kh, kw = [(1, 1), (3, 3), (3, 3), (3, 3), (5, 5), (3, 2), (2, 3)][int(r.integers(7))]
+        stride = (int(r.integers(1, 3)), int(r.integers(1, 3)))
+        pad = (int(r.integers(0, kh // 2 + 1)), int(r.integers(0, kw // 2 + 1)))
+        if h + 2 * pad[0] < kh or w + 2 * pad[1] < kw or n * c * h * w * o * kh * kw > 3e9:
+            continue
+        odt = torch.int32 if dtype == "i8" else (torch.bfloat16, torch.float32)[int(r.integers(2))]
+        cases.append((dtype, n, c, h, w, o, kh, kw, stride, pad, odt, bool(r.integers(2)), bool(r.integers(2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_conv_cases(20210905, 48))
+def test_conv2d_random_shapes(case):
+    """Both forms on seeded random shapes, with and without the fused residual and ReLU."""
+    dtype, n, c, h, w, o, kh, kw, stride, pad, odt, with_res, relu = case
+    x, wt = conv_inputs(case[:11])
+    ho, wo_ = (h + 2 * pad[0] - kh) // stride[0] + 1, (w + 2 * pad[1] - kw) // stride[1] + 1
+    res = None
+    if with_res:
+        res = (synth.uniform_int32((n, o, ho, wo_), -50000, 50000, 1701) if odt == torch.int32 else
+               synth.normal_bf16((n, o, ho, wo_), 1.0, 1702) if odt == torch.bfloat16 else
+               synth.normal_f32((n, o, ho, wo_), 1.0, 1703))
+    want = brute.conv2d(to_oracle(x), to_oracle(wt), stride, pad)
+    if res is not None:
+        want = want + to_oracle(res)
+    if relu:
+        want = np.maximum(want, 0)
+    act = gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE
+    outs = []
+    for fn in (gs.conv2d_direct, gs.conv2d_im2col):
+        got = fn(x.to(DEV), wt.to(DEV), stride, pad, residual=None if res is None else res.to(DEV), act=act, out_dtype=odt)
+        assert_parity(got, want, what=f"{fn.__name__} {case}")
+        outs.append(got)
+    if dtype == "i8":
+        assert torch.equal(outs[0], outs[1])
+
+
 def test_conv2d_direct_equals_im2col_bitwise_int8():
     """The rewrite of Sec. 5.3 preserves the result: both forms agree bit for bit on integers."""
     case = ("i8", 4, 32, 17, 19, 40, 3, 3, (1, 1), (1, 1), torch.int32)
