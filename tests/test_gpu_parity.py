@@ -735,3 +735,72 @@ def test_depthwise_extremes_and_empty():
     assert torch.isinf(gf[0, 0, :2, 6:]).all() and torch.isfinite(gf[0, 0, 2:]).all() and torch.isfinite(gf[0, 0, :, :6]).all()
     empty = torch.zeros((0, 4, 8, 8), dtype=torch.bfloat16, device=DEV)
     assert gs.depthwise_conv2d(empty, torch.ones((4, 3, 3), dtype=torch.bfloat16, device=DEV), (1, 1), (1, 1)).shape == (0, 4, 8, 8)
+
+
+# ---------------------------------------------------------------------------------------------
+# seeded random sweeps of the window kernels
+# ---------------------------------------------------------------------------------------------
+
+def _random_window_cases(seed, count):
+    r = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        dtype = ("i8", "bf16", "f32", "i32")[int(r.integers(4))]
+        n, c = int(r.integers(1, 4)), int(r.integers(1, 20))
+        h, w = int(r.integers(3, 70)), int(r.integers(3, 70))
+        k = (int(r.integers(1, 5)), int(r.integers(1, 5)))
+        s = (int(r.integers(1, 4)), int(r.integers(1, 4)))
+        p = (int(r.integers(0, k[0])), int(r.integers(0, k[1])))
+        if h + 2 * p[0] < k[0] or w + 2 * p[1] < k[1]:
+            continue
+        cases.append((dtype, (n, c, h, w), k, s, p))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_window_cases(20210906, 40))
+def test_windows_random_shapes(case):
+    """Pooling (fused windows + reduceMax / reduceSum) and the explicit gather on seeded random planes,
+    windows, strides and paddings; maxima and gathers bit-exact, sums within the accumulation bound."""
+    dtype, shape, k, s, p = case
+    x = gen(dtype, shape, 3500 + shape[2] + shape[3])
+    xd = x.to(DEV)
+    xo = to_oracle(x)
+    got = gs.windows_reduce(xd, 2, k, s, p, p, gs.GS_MAX)
+    np.testing.assert_array_equal(to_oracle(got), pg.max_pool2d(ap.tensor(xo), k, s, p, LOWEST[dtype]).materialize())
+    win = gs.access_windows(xd, 2, k, s, p, p, gs.GS_PAD_ZERO)
+    want_win = oracle_windows(x, 2, k, s, p, p, 0).materialize()
+    np.testing.assert_array_equal(to_oracle(win), want_win)
+    odt = {"i8": torch.int32, "i32": torch.int32, "bf16": torch.float32, "f32": torch.float32}[dtype]
+    tot = gs.windows_reduce(xd, 2, k, s, p, p, gs.GS_SUM, out_dtype=odt)
+    want_sum = want_win.sum(axis=(4, 5))
+    if dtype in ("i8", "i32"):
+        np.testing.assert_array_equal(to_oracle(tot), want_sum)
+    else:
+        assert_parity(tot, want_sum, float_tol=1e-4, what=str(case))
+
+
+def _random_depthwise_cases(seed, count):
+    r = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        dtype = ("bf16", "i8")[int(r.integers(2))]
+        n, c = int(r.integers(1, 4)), int(r.integers(1, 40))
+        h, w = int(r.integers(3, 60)), int(r.integers(3, 60))
+        kh, kw = [(3, 3), (3, 3), (5, 5), (1, 1), (2, 3), (4, 2)][int(r.integers(6))]
+        s = (int(r.integers(1, 3)), int(r.integers(1, 3)))
+        p = (int(r.integers(0, kh)), int(r.integers(0, kw)))
+        if h + 2 * p[0] < kh or w + 2 * p[1] < kw:
+            continue
+        odt = torch.int32 if dtype == "i8" else (torch.bfloat16, torch.float32)[int(r.integers(2))]
+        cases.append((dtype, n, c, h, w, kh, kw, s, p, odt, bool(r.integers(2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_depthwise_cases(20210907, 30))
+def test_depthwise_random_shapes(case):
+    dtype, n, c, h, w_, kh, kw, stride, pad, odt, relu = case
+    x = gen(dtype, (n, c, h, w_), 3600 + c + h)
+    w = gen(dtype, (c, kh, kw), 3700 + c + kh, 1.0 / np.sqrt(kh * kw) if dtype == "bf16" else 1.0)
+    got = gs.depthwise_conv2d(x.to(DEV), w.to(DEV), stride, pad, gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE, odt)
+    want = oracle_depthwise(x, w, stride, pad)
+    assert_parity(got, np.maximum(want, 0) if relu else want, what=str(case))
