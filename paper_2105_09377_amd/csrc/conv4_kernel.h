@@ -92,10 +92,12 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool producer = wave >= 4;
   const int M = int(g.M);
-  // A tile covers g.tps <= TP positions, g.tps / WP per consumer wave column (a multiple of 4);
-  // the MFMA blocks are TP wide and the columns past a wave's share are computed on a valid
-  // stand-in position and dropped.  The host shrinks tiles when that fills more compute units.
-  const int tps = g.tps, wpv = tps / WP;
+  // A tile covers g.tps <= TP positions (a multiple of 8), dealt to the consumer wave columns in
+  // groups of eight (the first columns take the odd groups), so that every wave's share starts and
+  // ends on a multiple of 8; the MFMA blocks are TP wide and the columns past a wave's share are
+  // computed on a valid stand-in position and dropped.  The host shrinks tiles when that fills
+  // more compute units.
+  const int tps = g.tps;
   const int tiles_m = (M + tps - 1) / tps;
   // A work item ("tile" below) is (position tile, channel tile, K split): the split index runs
   // fastest so that workgroups launched together share a patch.
@@ -512,6 +514,9 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   // Consumers
   // ===========================================================================================
   const int wo = wave / WP, wp = wave % WP;
+  const int wgroups = (tps >> 3) / WP, wextra = (tps >> 3) % WP;
+  const int wstart = 8 * (wp * wgroups + (wp < wextra ? wp : wextra));     // first position of this wave column
+  const int wpv = 8 * (wgroups + (wp < wextra ? 1 : 0));                   // and how many it covers
   // A-fragment address inside a 1 KB weight block: row (lane % 32), column lane / 32, swizzled.
   const int afrag = (lane & 31) * 32 + (((lane >> 5) ^ ((((lane & 31) >> 2) ^ ((lane & 31) >> 3)) & 1)) << 4) +
                     wo * (WOT / 32) * 1024;
@@ -528,7 +533,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     bool pos_ok[NJ];
 #pragma unroll
     for (int n = 0; n < NJ; ++n) {
-      const int m = m0 + wp * wpv + n * 32 + (lane & 31);
+      const int m = m0 + wstart + n * 32 + (lane & 31);
       pos_ok[n] = n * 32 + (lane & 31) < wpv && m < M;
       pbase[n] = (lane >> 5) * 16;
       out_base[n] = 0;
@@ -572,9 +577,15 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
         *reinterpret_cast<i32x4*>(row + gi * 32) = __builtin_bit_cast(i32x4, q);
       });
     };
-    const int gq = lane % GR, rsub = lane / GR;
-    const int mm = m0 + wp * wpv + gq * 4;
-    const bool grp_ok = gq * 4 < wpv && mm < M;
+    // bfloat16 results of planes that are multiples of 8 go out 8 positions (16 bytes) per lane:
+    // half as many store instructions, and a store costs the wave a few hundred cycles of issue
+    // time whatever its width.
+    const bool wide = vec_epi && ksplit == 1 && a.out_dtype == GS_BF16 && g.HWo % 8 == 0 &&
+                      !__is_same(typename TR::acc_t, int32_t);
+    const int pgw = wide ? 8 : 4;                    // positions per lane
+    const int gq = wide ? lane % (GR / 2) : lane % GR, rsub = wide ? lane / (GR / 2) : lane / GR;
+    const int mm = m0 + wstart + gq * pgw;
+    const bool grp_ok = gq * pgw < wpv && mm < M;
     const int gimg = int(g.dHWo.div(uint32_t(grp_ok ? mm : 0)));
     const uint32_t gbase = uint32_t(gimg) * uint32_t(a.O) * uint32_t(g.HWo) + uint32_t(mm - gimg * g.HWo);
     // Destination: the output, or with a split channel sum this split's slice of the partials
@@ -601,10 +612,28 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
         }
       });
     };
+    // The same for 8 positions per lane: twice the rows per step, half the steps, 16 bytes each
+    // (kept in two of the 8-byte registers).
+    auto request_residual_wide = [&]() {
+      static_for<MI>([&](auto m_) {
+        constexpr int m = decltype(m_)::value;
+#pragma unroll
+        for (int it = 0; it < NIT / 2; ++it) {
+          const int o = o0 + wo * WOT + m * 32 + it * (2 * ROWS_PER_IT) + rsub;
+          const uint32_t addr = (grp_ok && o < a.O) ? gbase + uint32_t(o) * uint32_t(g.HWo) : 0u;
+          const uint4 r = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.residual) + addr);
+          resv[m][2 * it] = make_uint2(r.x, r.y);
+          resv[m][2 * it + 1] = make_uint2(r.z, r.w);
+        }
+      });
+    };
 
     for (int ch = 0; ch < nchunk; ++ch) {
       const int buf = ch & 1;
-      if (ch == nchunk - 1 && vec_epi && res_early) request_residual();
+      if (ch == nchunk - 1 && vec_epi && res_early) {
+        if (wide) request_residual_wide();
+        else request_residual();
+      }
       const uint8_t* wb = wl + wslot * wbytes + afrag;
       const uint8_t* pb = pl + buf * pbytes;
       if constexpr (KH > 0) {
@@ -728,10 +757,52 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           }
         });
       };
+      // bfloat16, 8 positions per lane
+      auto write_back_wide = [&]() {
+        constexpr int RPI = 2 * ROWS_PER_IT, NW = NIT / 2;
+        static_for<MI>([&](auto m_) {
+          constexpr int m = decltype(m_)::value;
+          static_for<NJ>([&](auto n_) {
+            constexpr int n = decltype(n_)::value;
+            stage_block(acc[m][n], n);
+          });
+          i32x4 raw[NW][2];
+#pragma unroll
+          for (int it = 0; it < NW; ++it) {
+            const uint8_t* src = stage + (it * RPI + rsub) * RS + gq * 32;
+            raw[it][0] = *reinterpret_cast<const i32x4*>(src);
+            raw[it][1] = *reinterpret_cast<const i32x4*>(src + 16);
+          }
+#pragma unroll
+          for (int it = 0; it < NW; ++it) {
+            const int o = o0 + wo * WOT + m * 32 + it * RPI + rsub;
+            const uint32_t addr = gbase + uint32_t(o) * uint32_t(g.HWo);
+            const bool ok = grp_ok && o < a.O;
+            float f[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = __int_as_float(raw[it][e / 4][e % 4]);
+            if (has_res) {
+#pragma unroll
+              for (int h = 0; h < 2; ++h) {
+                const uint32_t qx = resv[m][2 * it + h].x, qy = resv[m][2 * it + h].y;
+                f[4 * h + 0] += __uint_as_float(qx << 16); f[4 * h + 1] += __uint_as_float(qx & 0xffff0000u);
+                f[4 * h + 2] += __uint_as_float(qy << 16); f[4 * h + 3] += __uint_as_float(qy & 0xffff0000u);
+              }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = relu ? fmaxf(f[e], 0.0f) : f[e];
+            i32x4 w4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w4[e] = int32_t(pack_bf16x2(f[2 * e], f[2 * e + 1]));
+            if (ok) *reinterpret_cast<i32x4*>(static_cast<uint16_t*>(outp) + addr) = w4;
+          }
+        });
+      };
       if constexpr (__is_same(typename TR::acc_t, int32_t)) {
         write_back(std::integral_constant<int, 0>{});
       } else {
-        if (odt == GS_BF16) write_back(std::integral_constant<int, 2>{});
+        if (wide) write_back_wide();
+        else if (odt == GS_BF16) write_back(std::integral_constant<int, 2>{});
         else write_back(std::integral_constant<int, 1>{});
       }
     } else {
