@@ -400,6 +400,49 @@ def test_conv2d_few_channels_residual_relu(odt):
     assert_parity(got, want, what="few channels, residual + relu")
 
 
+def _random_few_channel_cases(seed, count):
+    """Seeded shapes for the few-channel kernel: 1..4 channels (8 for int8), windows of 3..7, rows
+    that are and are not whole 16-byte vectors, output heights on and off the multiples of four
+    (a task is four output rows), output widths on and off the multiples of 4 and 8 and past 128."""
+    r = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        dtype = ("bf16", "bf16", "i8")[int(r.integers(3))]
+        n = int(r.integers(1, 4))
+        c = int(r.integers(1, 5)) if dtype == "bf16" else int(r.choice([1, 3, 4, 8]))
+        h = int(r.integers(7, 60))
+        w = int(r.choice([8, 16, 24, 31, 32, 40, 50, 56, 64, 100, 160, 272]))
+        o = int(r.choice([5, 32, 64, 70]))
+        k = int(r.choice([3, 5, 7]))
+        stride = (int(r.integers(1, 3)), int(r.integers(1, 3)))
+        pad = (int(r.integers(0, k // 2 + 1)), int(r.integers(0, k // 2 + 1)))
+        if h + 2 * pad[0] < k or w + 2 * pad[1] < k:
+            continue
+        odt = torch.int32 if dtype == "i8" else (torch.bfloat16, torch.float32)[int(r.integers(2))]
+        cases.append((dtype, n, c, h, w, o, k, k, stride, pad, odt, bool(r.integers(2)), bool(r.integers(2))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_few_channel_cases(20210908, 40))
+def test_conv2d_few_channels_random_shapes(case):
+    dtype, n, c, h, w, o, kh, kw, stride, pad, odt, with_res, relu = case
+    x, wt = conv_inputs(case[:11])
+    ho, wo_ = (h + 2 * pad[0] - kh) // stride[0] + 1, (w + 2 * pad[1] - kw) // stride[1] + 1
+    res = None
+    if with_res:
+        res = (synth.uniform_int32((n, o, ho, wo_), -50000, 50000, 1711) if odt == torch.int32 else
+               synth.normal_bf16((n, o, ho, wo_), 1.0, 1712) if odt == torch.bfloat16 else
+               synth.normal_f32((n, o, ho, wo_), 1.0, 1713))
+    want = brute.conv2d(to_oracle(x), to_oracle(wt), stride, pad)
+    if res is not None:
+        want = want + to_oracle(res)
+    if relu:
+        want = np.maximum(want, 0)
+    got = gs.conv2d_direct(x.to(DEV), wt.to(DEV), stride, pad, residual=None if res is None else res.to(DEV),
+                           act=gs.GS_ACT_RELU if relu else gs.GS_ACT_NONE, out_dtype=odt)
+    assert_parity(got, want, what=str(case))
+
+
 def test_conv2d_minus_128_and_empty_batch():
     x = torch.full((1, 32, 6, 6), -128, dtype=torch.int8)
     w = torch.full((8, 32, 3, 3), -128, dtype=torch.int8)
