@@ -527,6 +527,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   for (; tile < n_tiles; tile += gridDim.x) {
     tile_range(tile, &m0, &mend, &o0);
     const TileSegs ts = tile_segs(m0, mend, g);
+    // The extents of the tile's first two segments are the same for every lane (scalar work);
+    // only tiles that touch more than two images walk the segments per lane.
+    int ihlo0 = 0, rows0 = 0, ihlo1 = 0, rows1 = 0;
+    seg_extent(ts, 0, g, a.Sh, a.Ph, a.Kh, &ihlo0, &rows0);
+    if (ts.nseg > 1) seg_extent(ts, 1, g, a.Sh, a.Ph, a.Kh, &ihlo1, &rows1);
     // Per-lane window origins in the patch, and output addresses.
     int pbase[NJ];
     uint32_t out_base[NJ];
@@ -540,10 +545,15 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       if (pos_ok[n]) {
         const int img = int(g.dHWo.div(uint32_t(m))), p = m - img * g.HWo;
         const int ho = int(g.dWo.div(uint32_t(p))), wo_ = p - ho * a.Wo;
-        int base = 0, ihlo = 0, rows = 0;              // patch rows in front of this image's segment
-        for (int s = 0; s <= img - ts.n_first; ++s) {
-          base += rows;
-          seg_extent(ts, s, g, a.Sh, a.Ph, a.Kh, &ihlo, &rows);
+        const int si = img - ts.n_first;
+        int base = si ? rows0 : 0, ihlo = si ? ihlo1 : ihlo0;   // patch rows in front of this image's segment
+        if (ts.nseg > 2) {                             // uniform; small planes only
+          int rows = 0;
+          base = 0;
+          for (int s = 0; s <= si; ++s) {
+            base += rows;
+            seg_extent(ts, s, g, a.Sh, a.Ph, a.Kh, &ihlo, &rows);
+          }
         }
         const int row = base + (ho * a.Sh - a.Ph - ihlo);
         const int col = wo_ * a.Sw - a.Pw + g.XO;
