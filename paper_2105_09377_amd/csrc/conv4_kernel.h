@@ -703,6 +703,9 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     // maximum with a run-time lower bound, so the write-back is straight-line code.
     if (vec_epi) {
       const int lo_i = relu ? 0 : INT_MIN;
+      // ReLU as one maximum per value with a run-time second operand: zero, or a NaN, which
+      // fmaxf ignores (it returns the other operand), so that nothing changes without ReLU.
+      const float lo_f = relu ? 0.0f : __builtin_nanf("");
       auto write_back = [&](auto kind_) {
         constexpr int kind = decltype(kind_)::value;   // 0: int32, 1: f32, 2: bf16
         static_for<MI>([&](auto m_) {
@@ -748,7 +751,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
                 }
                 i32x4 w4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w4[e] = __float_as_int(relu ? fmaxf(f[e], 0.0f) : f[e]);
+                for (int e = 0; e < 4; ++e) w4[e] = __float_as_int(fmaxf(f[e], lo_f));
                 if (ok) *reinterpret_cast<i32x4*>(static_cast<float*>(outp) + addr) = w4;
               } else {
                 if (has_res) {
@@ -757,7 +760,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
                   f[2] += __uint_as_float(qy << 16); f[3] += __uint_as_float(qy & 0xffff0000u);
                 }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) f[e] = relu ? fmaxf(f[e], 0.0f) : f[e];
+                for (int e = 0; e < 4; ++e) f[e] = fmaxf(f[e], lo_f);
                 uint2 w2;
                 w2.x = pack_bf16x2(f[0], f[1]);
                 w2.y = pack_bf16x2(f[2], f[3]);
@@ -800,7 +803,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
               }
             }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] = relu ? fmaxf(f[e], 0.0f) : f[e];
+            for (int e = 0; e < 8; ++e) f[e] = fmaxf(f[e], lo_f);
             i32x4 w4;
 #pragma unroll
             for (int e = 0; e < 4; ++e) w4[e] = int32_t(pack_bf16x2(f[2 * e], f[2 * e + 1]));
