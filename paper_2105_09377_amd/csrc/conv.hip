@@ -165,12 +165,21 @@ hipError_t launch_conv3_i8_t0(const ConvArgs&, const ConvGeom&, hipStream_t);
 hipError_t launch_conv3_i8_t1(const ConvArgs&, const ConvGeom&, hipStream_t);
 hipError_t launch_conv3_i8_t2(const ConvArgs&, const ConvGeom&, hipStream_t);
 
-// 64 x 256 tiles while they number at least three quarters of the compute units, or, for unit
-// strides, when halving each tile's channel sum (nchunk chunks; the split needs a multiple of 8)
-// gets them there.  (With larger strides a 256-position patch is too large a load per chunk.)
-static bool conv_prefers_wide_tile(int64_t M, int O, int nchunk, bool unit_stride) {
-  const int64_t tiles = ceil_div(M, 256) * ceil_div(O, 64);
-  return tiles >= 192 || (unit_stride && nchunk % 8 == 0 && tiles * 2 >= 192 && tiles * 2 <= 256);
+// 64 x 256 or 64 x 128 tiles: whichever needs less time by rounds x cost per tile, a wide tile
+// costing 1.44 narrow ones (measured: 196 wide tiles of 256 channels at 14x14 take 23.7 us in one
+// round, the same layer in 392 narrow tiles 33.0 us in two).  Few tiles therefore go narrow (more
+// compute units busy): 256 channels at 14x14, batch 32, 17.9 us in 196 narrow tiles against 23.7
+// in 100 wide ones with a two-way split of the channel sum.  Planes that are no multiple of four
+// positions (7x7) are the exception: their results leave a tile one value at a time, which with a
+// residual costs more than the combining pass of a split sum (39.5 against 36 us at batch 64, 29.4
+// against 35.2 without a residual), so for unit strides they keep wide tiles whenever a two-way
+// split fills the chip.
+static bool conv_prefers_wide_tile(int64_t M, int O, int nchunk, bool unit_stride, int HWo) {
+  const int64_t cus = 256;
+  const int64_t wide = ceil_div(M, 256) * ceil_div(O, 64), narrow = ceil_div(M, 128) * ceil_div(O, 64);
+  if (HWo % 4 != 0)
+    return wide >= 192 || (unit_stride && nchunk % 8 == 0 && wide * 2 >= 192 && wide * 2 <= 256);
+  return double(ceil_div(wide, cus)) * 1.44 < double(ceil_div(narrow, cus));
 }
 
 template <typename TR>
@@ -183,7 +192,7 @@ static hipError_t launch_conv3(const ConvArgs& a, const ConvGeom& g, hipStream_t
   auto t1 = [&]() { return i8 ? launch_conv3_i8_t1(a, g, s) : launch_conv3_bf16_t1(a, g, s); };
   auto t2 = [&]() { return i8 ? launch_conv3_i8_t2(a, g, s) : launch_conv3_bf16_t2(a, g, s); };
   hipError_t e = hipErrorInvalidValue;
-  const bool wide = conv_prefers_wide_tile(g.M, a.O, a.Cpad / (32 / TR::kEsz), a.Sh * a.Sw == 1);
+  const bool wide = conv_prefers_wide_tile(g.M, a.O, a.Cpad / (32 / TR::kEsz), a.Sh * a.Sw == 1, g.HWo);
   e = wide ? t1() : t2();
   if (e != hipErrorInvalidValue) return e;
   e = wide ? t2() : t1();
@@ -251,7 +260,7 @@ conv_splitk_finish_vec_kernel(const AccT* __restrict__ partial, int ksplit, int6
 int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo, bool unit_stride) {
   const int64_t M = int64_t(N) * Ho * Wo;
   const int nchunk = conv_cpad(in_dtype, C) / (in_dtype == GS_I8 ? 32 : 16);
-  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O, nchunk, unit_stride) ? 256 : 128) * ceil_div(O, 64);
+  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O, nchunk, unit_stride, Ho * Wo) ? 256 : 128) * ceil_div(O, 64);
   const int cus = 256;
   if (tiles * 4 <= cus && nchunk % 16 == 0) return 4;
   if (tiles * 2 <= cus && nchunk % 8 == 0) return 2;
