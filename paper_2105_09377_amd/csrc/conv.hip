@@ -173,11 +173,12 @@ hipError_t launch_conv3_i8_t2(const ConvArgs&, const ConvGeom&, hipStream_t);
 // positions (7x7) are the exception: their results leave a tile one value at a time, which with a
 // residual costs more than the combining pass of a split sum (39.5 against 36 us at batch 64, 29.4
 // against 35.2 without a residual), so for unit strides they keep wide tiles whenever a two-way
-// split fills the chip.
-static bool conv_prefers_wide_tile(int64_t M, int O, int nchunk, bool unit_stride, int HWo) {
+// split fills the chip -- when there is a residual to add (`with_residual`; the scratch memory is
+// sized as if there were one, a call without one simply leaves the partial sums unused).
+static bool conv_prefers_wide_tile(int64_t M, int O, int nchunk, bool unit_stride, int HWo, bool with_residual) {
   const int64_t cus = 256;
   const int64_t wide = ceil_div(M, 256) * ceil_div(O, 64), narrow = ceil_div(M, 128) * ceil_div(O, 64);
-  if (HWo % 4 != 0)
+  if (HWo % 4 != 0 && with_residual)
     return wide >= 192 || (unit_stride && nchunk % 8 == 0 && wide * 2 >= 192 && wide * 2 <= 256);
   return double(ceil_div(wide, cus)) * 1.44 < double(ceil_div(narrow, cus));
 }
@@ -192,7 +193,8 @@ static hipError_t launch_conv3(const ConvArgs& a, const ConvGeom& g, hipStream_t
   auto t1 = [&]() { return i8 ? launch_conv3_i8_t1(a, g, s) : launch_conv3_bf16_t1(a, g, s); };
   auto t2 = [&]() { return i8 ? launch_conv3_i8_t2(a, g, s) : launch_conv3_bf16_t2(a, g, s); };
   hipError_t e = hipErrorInvalidValue;
-  const bool wide = conv_prefers_wide_tile(g.M, a.O, a.Cpad / (32 / TR::kEsz), a.Sh * a.Sw == 1, g.HWo);
+  const bool wide = conv_prefers_wide_tile(g.M, a.O, a.Cpad / (32 / TR::kEsz), a.Sh * a.Sw == 1, g.HWo,
+                                           a.residual != nullptr);
   e = wide ? t1() : t2();
   if (e != hipErrorInvalidValue) return e;
   e = wide ? t2() : t1();
@@ -260,7 +262,7 @@ conv_splitk_finish_vec_kernel(const AccT* __restrict__ partial, int ksplit, int6
 int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo, bool unit_stride) {
   const int64_t M = int64_t(N) * Ho * Wo;
   const int nchunk = conv_cpad(in_dtype, C) / (in_dtype == GS_I8 ? 32 : 16);
-  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O, nchunk, unit_stride, Ho * Wo) ? 256 : 128) * ceil_div(O, 64);
+  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O, nchunk, unit_stride, Ho * Wo, true) ? 256 : 128) * ceil_div(O, 64);
   const int cus = 256;
   if (tiles * 4 <= cus && nchunk % 16 == 0) return 4;
   if (tiles * 2 <= cus && nchunk % 8 == 0) return 2;
@@ -288,6 +290,17 @@ static hipError_t launch_conv_t(const ConvArgs& a_in, hipStream_t s) {
   g.dHWo = FastDiv::make(uint32_t(g.HWo > 0 ? g.HWo : 1));
   g.dWo = FastDiv::make(uint32_t(a.Wo > 0 ? a.Wo : 1));
   if (g.M == 0 || a.O == 0) return hipSuccess;
+  // A split that was planned around wide tiles for the sake of a residual (see
+  // conv_prefers_wide_tile) is dropped when the call has none: narrow tiles then fill the chip.
+  if (a.ksplit > 1 && !a.residual) {
+    const int nchunk = a.Cpad / (32 / TR::kEsz);
+    const bool unit = a.Sh * a.Sw == 1;
+    if (conv_prefers_wide_tile(g.M, a.O, nchunk, unit, g.HWo, true) &&
+        !conv_prefers_wide_tile(g.M, a.O, nchunk, unit, g.HWo, false)) {
+      a.ksplit = 1;
+      a.partial = nullptr;
+    }
+  }
   if (a.wnat) {                        // fewer channels than a chunk: windows formed as im2col rows in LDS
     ConvArgs b = a;
     b.wr = a.wnat;
