@@ -49,9 +49,9 @@ KERNEL_SOURCES = {
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (26.99e6 + 25.70e6, "conv", "fcd87d2306b542da5c97094ea96b61cce82c97efe00aa0c5c8a6a94da2a2a8c4"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
-    "conv3x3": (14.14e6 + 12.85e6, "conv", "fcd87d2306b542da5c97094ea96b61cce82c97efe00aa0c5c8a6a94da2a2a8c4"),
-    "conv3x3_b64": (26.99e6 + 25.70e6, "conv", "fcd87d2306b542da5c97094ea96b61cce82c97efe00aa0c5c8a6a94da2a2a8c4"),
+    "resnet18": (26.99e6 + 25.70e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
+    "conv3x3": (14.14e6 + 12.85e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),
+    "conv3x3_b64": (26.99e6 + 25.70e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),
     "im2col_gather": (12.97e6 + 115.65e6, "windows", "7741b56696f4637c8ca3c5a547f3f4d48b8d1f212974cd69d7997399800e3506"),
     "maxpool": (103.00e6 + 25.69e6, "reduce", "4b5f1c3525283bcdbdfedb76eecfe0a01ed922a83e0882400e3fedff4fb6d82c"),
     "reduce": (268.44e6 + 0.52e6, "reduce", "4b5f1c3525283bcdbdfedb76eecfe0a01ed922a83e0882400e3fedff4fb6d82c"),
@@ -59,7 +59,7 @@ TRAFFIC = {
     "dense_blocked": (50.63e6 + 16.78e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
     "dense": (1611.42e6 + 281.85e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
     "mlp_scaled": (28.91e6 + 16.78e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
-    "conv3x3_i8": (7.29e6 + 25.71e6, "conv", "fcd87d2306b542da5c97094ea96b61cce82c97efe00aa0c5c8a6a94da2a2a8c4"),
+    "conv3x3_i8": (7.29e6 + 25.71e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),
     "dense_i8": (805.93e6 + 287.46e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
     "dense_fp8": (806.21e6 + 134.22e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
     "depthwise": (103.03e6 + 102.76e6, "depthwise", "b55bbabacf3938893acb7ff9df30d54119d03cc82754824aaf4170d2facde200"),
