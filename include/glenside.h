@@ -148,7 +148,10 @@ int glenside_depthwise_conv2d(const gs_ap* activations, const gs_ap* weights, co
  *   _pack_weights  : writes the weight access pattern ((O),(C,Kh,Kw)) into `packed` in the order
  *                    the contraction reads it, (O, Kh, Kw, C) with C padded to a 32-byte step --
  *                    the weight-side layout change that the systolic-array rewrite (Sec. 5.2) makes
- *                    explicit with (transpose ?a1 ...).  Needs glenside_conv2d_direct_workspace bytes.
+ *                    explicit with (transpose ?a1 ...) -- and, when C is a whole number of such
+ *                    steps, once more cut into blocks of 32 output channels x one step of one
+ *                    tap (1 KB each, the unit the kernel moves on chip), (O/32, C-step, Kh, Kw).
+ *                    Needs glenside_conv2d_direct_workspace bytes.
  *   _direct_packed : the convolution proper, reading weights only from `packed`; `weights` gives
  *                    shape and dtype, its data pointer is not read.  `packed` needs the bytes that
  *                    _pack_weights needs; when it has glenside_conv2d_direct_workspace bytes for

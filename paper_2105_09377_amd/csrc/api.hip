@@ -347,7 +347,7 @@ size_t glenside_conv2d_direct_workspace(const gs_ap* act, const gs_ap* w, const 
   ConvShape cs;
   if (conv_shape(act, w, stride, pad, &cs)) return 0;
   const int64_t wbytes = round_up(int64_t(conv_weight_workspace(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw)), 256) + 256;
-  const int ks = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo, cs.Sh * cs.Sw == 1);
+  const int ks = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo);
   const int64_t scratch = ks > 1 ? int64_t(ks) * cs.N * cs.O * cs.Ho * cs.Wo * 4 : 0;
   return size_t(wbytes + scratch);
 }
@@ -398,7 +398,7 @@ int glenside_conv2d_direct_packed(const gs_ap* act, const gs_ap* w, const int64_
   memset(&a, 0, sizeof(a));
   a.ksplit = 1;
   if (need > wneed && packed_bytes >= need) {
-    a.ksplit = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo, cs.Sh * cs.Sw == 1);
+    a.ksplit = conv_pick_ksplit(act->dtype, cs.N, cs.C, cs.O, cs.Ho, cs.Wo);
     a.partial = static_cast<uint8_t*>(packed) + wneed;
   }
   a.act = act->data;
@@ -412,6 +412,8 @@ int glenside_conv2d_direct_packed(const gs_ap* act, const gs_ap* w, const int64_
   a.Cpad = int(round_up(cs.C, act->dtype == GS_I8 ? 32 : 16));
   if (conv_is_smallc(act->dtype, cs.C))
     a.wnat = static_cast<const uint8_t*>(packed) + conv_smallc_weight_offset(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw);
+  if (conv_blocked_weight_bytes(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw))
+    a.wblk = static_cast<const uint8_t*>(packed) + conv_blocked_weight_offset(act->dtype, cs.O, cs.C, cs.Kh, cs.Kw);
   a.relu = actfn == GS_ACT_RELU;
   return launch_status(launch_conv(a, static_cast<hipStream_t>(stream)));
 }

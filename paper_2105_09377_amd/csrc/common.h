@@ -269,6 +269,7 @@ struct ConvArgs {
   const void* act;        // N x C x H x W
   const void* wr;         // repacked weights: O x (Kh*Kw) x Cpad, channel fastest, zero padded
   const void* wnat;       // fewer channels than a chunk: ((O up to 64s),(K up to 32 B)) copy, else null
+  const void* wblk;       // whole chunks only (C == Cpad): the copy in 1 KB blocks (see conv_blocked_weight_offset), else null
   void* out;              // N x O x Ho x Wo
   const void* residual;
   int in_dtype, out_dtype;
@@ -283,6 +284,14 @@ size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw);
 bool conv_is_smallc(int in_dtype, int C);
 size_t conv_smallc_weight_bytes(int in_dtype, int O, int C, int Kh, int Kw);
 size_t conv_smallc_weight_offset(int in_dtype, int O, int C, int Kh, int Kw);
+// Channel counts that are whole chunks (32 bytes per tap): a third copy behind the others, cut
+// into blocks of 1 KB = 32 output channels x one chunk of one tap, ordered [O / 32][chunk][tap],
+// each block the exact image of the LDS block the convolution's weight transfers fill (lane i of a
+// transfer moves bytes 16 i .. 16 i + 15), so that one transfer reads 1 KB of consecutive memory
+// instead of 32 pieces of 32 bytes from 32 rows.  Bytes of that copy (0 if there is none) and its
+// offset in the weight workspace.
+size_t conv_blocked_weight_bytes(int in_dtype, int O, int C, int Kh, int Kw);
+size_t conv_blocked_weight_offset(int in_dtype, int O, int C, int Kh, int Kw);
 hipError_t launch_conv_smallc_pack(const void* w, void* wn, int in_dtype, int O, int C, int Kh, int Kw,
                                    hipStream_t s);
 hipError_t launch_conv_smallc(const ConvArgs& a, hipStream_t s);   // reads a.wr = natural-order copy
@@ -293,7 +302,7 @@ hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int 
 // blocking rule: partial dot products combined by reduceSum over a pair); others ignore it.
 hipError_t launch_conv(const ConvArgs& a, hipStream_t s);
 // Split the channel sum of this shape?  Returns 1, 2 or 4 (host heuristic: few tiles, many chunks).
-int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo, bool unit_stride);
+int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo);
 
 struct ReduceArgs {       // out[r] = reduce over `cols` contiguous values
   const void* in;

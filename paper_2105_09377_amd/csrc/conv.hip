@@ -46,10 +46,51 @@ size_t conv_smallc_weight_offset(int in_dtype, int O, int C, int Kh, int Kw) {
   return size_t(round_up(int64_t(O) * Kh * Kw * conv_cpad(in_dtype, C) * int64_t(dtype_size(in_dtype)), 256));
 }
 
-size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw) {
+// The two copies in front of the blocked one.
+static size_t conv_weight_front_bytes(int in_dtype, int O, int C, int Kh, int Kw) {
   const size_t tap_major = size_t(O) * Kh * Kw * conv_cpad(in_dtype, C) * dtype_size(in_dtype);
   const size_t natural = conv_smallc_weight_bytes(in_dtype, O, C, Kh, Kw);
   return natural ? conv_smallc_weight_offset(in_dtype, O, C, Kh, Kw) + natural : tap_major;
+}
+
+size_t conv_blocked_weight_bytes(int in_dtype, int O, int C, int Kh, int Kw) {
+  if (C != conv_cpad(in_dtype, C)) return 0;
+  return size_t(round_up(O, 32)) * Kh * Kw * C * dtype_size(in_dtype);
+}
+
+size_t conv_blocked_weight_offset(int in_dtype, int O, int C, int Kh, int Kw) {
+  return size_t(round_up(int64_t(conv_weight_front_bytes(in_dtype, O, C, Kh, Kw)), 256));
+}
+
+size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw) {
+  const size_t blocked = conv_blocked_weight_bytes(in_dtype, O, C, Kh, Kw);
+  return blocked ? conv_blocked_weight_offset(in_dtype, O, C, Kh, Kw) + blocked
+                 : conv_weight_front_bytes(in_dtype, O, C, Kh, Kw);
+}
+
+// The blocked copy (see conv_blocked_weight_offset): element e of 16-byte piece i of block
+// (ob, chunk, tap) is w[ob * 32 + i / 2][chunk * CCH + h * G + e][tap], G = elements in 16 bytes,
+// CCH = 2 G, h = (i % 2) ^ (((r >> 2) ^ (r >> 3)) & 1) with r = i / 2 -- the swizzle the
+// consumers' fragment reads undo; rows past O are zero.
+template <typename T>
+__global__ void __launch_bounds__(256)
+conv_repack_blocked_kernel(const T* __restrict__ w, T* __restrict__ wb, int O, int C, int T_) {
+  constexpr int G = 16 / int(sizeof(T)), CCH = 2 * G;
+  const int nchunk = C / CCH;
+  const int64_t total = int64_t(round_up(O, 32)) * T_ * C;
+  for (int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; f < total;
+       f += int64_t(gridDim.x) * blockDim.x) {
+    const int e = int(f % G);
+    const int i = int((f / G) % 64);
+    const int64_t blk = f / (G * 64);
+    const int tap = int(blk % T_);
+    const int chunk = int((blk / T_) % nchunk);
+    const int64_t ob = blk / T_ / nchunk;
+    const int r = i >> 1, h = (i & 1) ^ (((r >> 2) ^ (r >> 3)) & 1);
+    const int64_t o = ob * 32 + r;
+    const int c = chunk * CCH + h * G + e;
+    wb[f] = o < O ? w[(o * C + c) * T_ + tap] : T(0);
+  }
 }
 
 hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int C, int Kh, int Kw,
@@ -66,6 +107,18 @@ hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int 
     hipLaunchKernelGGL((conv_repack_kernel<uint16_t>), grid, dim3(256), 0, s,
                        static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wr), O, C, Kh * Kw, Cpad);
   hipError_t e = hipGetLastError();
+  if (e == hipSuccess && conv_blocked_weight_bytes(in_dtype, O, C, Kh, Kw)) {
+    uint8_t* wb = static_cast<uint8_t*>(wr) + conv_blocked_weight_offset(in_dtype, O, C, Kh, Kw);
+    const int64_t tb = int64_t(round_up(O, 32)) * Kh * Kw * C, bb = ceil_div(tb, 256);
+    const dim3 gb(unsigned(bb < 65536 ? bb : 65536));
+    if (in_dtype == GS_I8)
+      hipLaunchKernelGGL((conv_repack_blocked_kernel<uint8_t>), gb, dim3(256), 0, s,
+                         static_cast<const uint8_t*>(w), wb, O, C, Kh * Kw);
+    else
+      hipLaunchKernelGGL((conv_repack_blocked_kernel<uint16_t>), gb, dim3(256), 0, s,
+                         static_cast<const uint16_t*>(w), reinterpret_cast<uint16_t*>(wb), O, C, Kh * Kw);
+    e = hipGetLastError();
+  }
   if (e == hipSuccess && conv_is_smallc(in_dtype, C))
     e = launch_conv_smallc_pack(w, static_cast<uint8_t*>(wr) + conv_smallc_weight_offset(in_dtype, O, C, Kh, Kw),
                                 in_dtype, O, C, Kh, Kw, s);
@@ -169,17 +222,11 @@ hipError_t launch_conv3_i8_t2(const ConvArgs&, const ConvGeom&, hipStream_t);
 // costing 1.44 narrow ones (measured: 196 wide tiles of 256 channels at 14x14 take 23.7 us in one
 // round, the same layer in 392 narrow tiles 33.0 us in two).  Few tiles therefore go narrow (more
 // compute units busy): 256 channels at 14x14, batch 32, 17.9 us in 196 narrow tiles against 23.7
-// in 100 wide ones with a two-way split of the channel sum.  Planes that are no multiple of four
-// positions (7x7) are the exception: their results leave a tile one value at a time, which with a
-// residual costs more than the combining pass of a split sum (39.5 against 36 us at batch 64, 29.4
-// against 35.2 without a residual), so for unit strides they keep wide tiles whenever a two-way
-// split fills the chip -- when there is a residual to add (`with_residual`; the scratch memory is
-// sized as if there were one, a call without one simply leaves the partial sums unused).
-static bool conv_prefers_wide_tile(int64_t M, int O, int nchunk, bool unit_stride, int HWo, bool with_residual) {
+// in 100 wide ones with a two-way split of the channel sum; 512 channels at 7x7, batch 64, with a
+// residual, 28 us in 200 narrow tiles against 34 in 104 wide ones split two ways.
+static bool conv_prefers_wide_tile(int64_t M, int O) {
   const int64_t cus = 256;
   const int64_t wide = ceil_div(M, 256) * ceil_div(O, 64), narrow = ceil_div(M, 128) * ceil_div(O, 64);
-  if (HWo % 4 != 0 && with_residual)
-    return wide >= 192 || (unit_stride && nchunk % 8 == 0 && wide * 2 >= 192 && wide * 2 <= 256);
   return double(ceil_div(wide, cus)) * 1.44 < double(ceil_div(narrow, cus));
 }
 
@@ -193,8 +240,7 @@ static hipError_t launch_conv3(const ConvArgs& a, const ConvGeom& g, hipStream_t
   auto t1 = [&]() { return i8 ? launch_conv3_i8_t1(a, g, s) : launch_conv3_bf16_t1(a, g, s); };
   auto t2 = [&]() { return i8 ? launch_conv3_i8_t2(a, g, s) : launch_conv3_bf16_t2(a, g, s); };
   hipError_t e = hipErrorInvalidValue;
-  const bool wide = conv_prefers_wide_tile(g.M, a.O, a.Cpad / (32 / TR::kEsz), a.Sh * a.Sw == 1, g.HWo,
-                                           a.residual != nullptr);
+  const bool wide = conv_prefers_wide_tile(g.M, a.O);
   e = wide ? t1() : t2();
   if (e != hipErrorInvalidValue) return e;
   e = wide ? t2() : t1();
@@ -259,10 +305,10 @@ conv_splitk_finish_vec_kernel(const AccT* __restrict__ partial, int ksplit, int6
   }
 }
 
-int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo, bool unit_stride) {
+int conv_pick_ksplit(int in_dtype, int N, int C, int O, int Ho, int Wo) {
   const int64_t M = int64_t(N) * Ho * Wo;
   const int nchunk = conv_cpad(in_dtype, C) / (in_dtype == GS_I8 ? 32 : 16);
-  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O, nchunk, unit_stride, Ho * Wo, true) ? 256 : 128) * ceil_div(O, 64);
+  const int64_t tiles = ceil_div(M, conv_prefers_wide_tile(M, O) ? 256 : 128) * ceil_div(O, 64);
   const int cus = 256;
   if (tiles * 4 <= cus && nchunk % 16 == 0) return 4;
   if (tiles * 2 <= cus && nchunk % 8 == 0) return 2;
@@ -290,17 +336,6 @@ static hipError_t launch_conv_t(const ConvArgs& a_in, hipStream_t s) {
   g.dHWo = FastDiv::make(uint32_t(g.HWo > 0 ? g.HWo : 1));
   g.dWo = FastDiv::make(uint32_t(a.Wo > 0 ? a.Wo : 1));
   if (g.M == 0 || a.O == 0) return hipSuccess;
-  // A split that was planned around wide tiles for the sake of a residual (see
-  // conv_prefers_wide_tile) is dropped when the call has none: narrow tiles then fill the chip.
-  if (a.ksplit > 1 && !a.residual) {
-    const int nchunk = a.Cpad / (32 / TR::kEsz);
-    const bool unit = a.Sh * a.Sw == 1;
-    if (conv_prefers_wide_tile(g.M, a.O, nchunk, unit, g.HWo, true) &&
-        !conv_prefers_wide_tile(g.M, a.O, nchunk, unit, g.HWo, false)) {
-      a.ksplit = 1;
-      a.partial = nullptr;
-    }
-  }
   if (a.wnat) {                        // fewer channels than a chunk: windows formed as im2col rows in LDS
     ConvArgs b = a;
     b.wr = a.wnat;

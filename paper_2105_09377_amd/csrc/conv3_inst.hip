@@ -76,8 +76,9 @@ static hipError_t launch_conv4(const ConvArgs& a, ConvGeom g, hipStream_t s) {
   const int ksplit = a.ksplit > 1 ? a.ksplit : 1;
   const int nchunk = a.Cpad / (32 / TR::kEsz);
   if (nchunk % (2 * ksplit) != 0) return hipErrorInvalidValue;   // the ring holds two or four chunks
-  // the producers address the packed weights by 32-bit byte offsets
-  if (int64_t(a.O) * a.Kh * a.Kw * a.Cpad * TR::kEsz >= (int64_t(1) << 32)) return hipErrorInvalidValue;
+  // the producers read the blocked weight copy, by 32-bit byte offsets
+  if (!a.wblk) return hipErrorInvalidValue;
+  if (round_up(a.O, 32) * a.Kh * a.Kw * a.Cpad * TR::kEsz >= (int64_t(1) << 32)) return hipErrorInvalidValue;
   // Positions per tile: TP, or fewer (in steps that keep each wave's share a multiple of 4) when
   // that lowers rounds x tile cost, a tile's cost being half fixed (the MFMA blocks stay TP wide)
   // and half proportional to its positions (patch traffic, write-back).  Only where that

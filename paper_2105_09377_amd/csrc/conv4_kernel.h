@@ -160,9 +160,11 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
     const int ptid = tid - 320;
     constexpr int PT = 192;                             // patch threads
     const uint8_t* act = static_cast<const uint8_t*>(a.act);
-    const uint8_t* wr = static_cast<const uint8_t*>(a.wr);
+    const uint8_t* wr = static_cast<const uint8_t*>(a.wblk);   // 1 KB blocks [O / 32][chunk][tap]
     const int64_t plane = int64_t(a.H) * a.W * ESZ;     // bytes per channel plane
-    const int64_t wr_row = int64_t(T) * a.Cpad * ESZ;   // bytes per output channel in wr
+    const uint32_t wr_chunk = uint32_t(T) * 1024u;       // bytes of one chunk of a 32-channel block
+    const uint32_t wr_blk = uint32_t(a.Cpad / CCH) * wr_chunk;   // and of all its chunks
+    const int n_oblk = (a.O + 31) / 32;
     const int XGn = a.W / VW;                           // pixel groups per row
     const FastDiv dXG = g.dXG;
     const int n_wq = T * OB;
@@ -303,10 +305,9 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       }
     };
     // Weight transfers: instruction q of a chunk covers tap q / OB, rows (q % OB) * 32 .. + 31 of
-    // the channel tile; lane i fills (row i / 2, position i % 2).  With static taps the per-lane
-    // byte offsets of all of them are fixed per channel tile.
-    const int wrow = lane >> 1;
-    const int wcol = ((lane & 1) ^ (((wrow >> 2) ^ (wrow >> 3)) & 1)) * 16;
+    // the channel tile, which the blocked weight copy holds as 1 KB of consecutive bytes in the
+    // order of the LDS block (row i / 2, swizzled position, for piece i): lane i moves piece i.
+    // With static taps the per-lane byte offsets of all of them are fixed per channel tile.
     constexpr int NWI = KH > 0 ? KH * KW * OB : 0;             // weight instructions per chunk (static taps)
     struct WSrc {
       uint32_t off[KH > 0 ? NWI : OB];   // static taps: per instruction; else per 32-row block
@@ -318,22 +319,22 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
 #pragma unroll
         for (int k = 0; k < NWI; ++k) {
           const int tap = k / OB, b = k % OB;
-          int o = o0_ + b * 32 + wrow;
-          o = o < a.O ? o : a.O - 1;                      // rows past O are never stored
-          w.off[k] = uint32_t(o * wr_row + wcol + int64_t(tap) * a.Cpad * ESZ);
+          int ob = o0_ / 32 + b;
+          ob = ob < n_oblk ? ob : n_oblk - 1;             // blocks past O are never stored
+          w.off[k] = uint32_t(ob) * wr_blk + uint32_t(tap) * 1024u + uint32_t(lane) * 16u;
         }
       } else {
 #pragma unroll
         for (int b = 0; b < OB; ++b) {
-          int o = o0_ + b * 32 + wrow;
-          o = o < a.O ? o : a.O - 1;
-          w.off[b] = uint32_t(o * wr_row + wcol);
+          int ob = o0_ / 32 + b;
+          ob = ob < n_oblk ? ob : n_oblk - 1;
+          w.off[b] = uint32_t(ob) * wr_blk + uint32_t(lane) * 16u;
         }
       }
     };
     WSrc wld;
     const uint32_t wl_addr = lds_addr_of(wl);
-    // `wbase` = wr + byte offset of the chunk within a weight row (scalar).
+    // `wbase` = wr + byte offset of the chunk within a 32-channel block (scalar).
     auto issue_weights = [&](const uint8_t* wbase, int slot) {
       if constexpr (KH > 0) {
 #pragma unroll
@@ -344,7 +345,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           uint32_t off = wld.off[0];
 #pragma unroll
           for (int bb = 1; bb < OB; ++bb) off = (b == bb) ? wld.off[bb] : off;
-          lds_dma16_off(wbase + int64_t(tap) * a.Cpad * ESZ, off, wl_addr + slot * wbytes + q * 1024);
+          lds_dma16_off(wbase + int64_t(tap) * 1024, off, wl_addr + slot * wbytes + q * 1024);
         }
       }
     };
@@ -401,7 +402,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       const uint8_t* base;      // scalar: start of the current chunk in the tensor the cursor reads
     };
     auto act_base = [&](int item) { return act + int64_t(split_of(item)) * nchunk * chunk_bytes; };
-    auto w_base = [&](int item) { return wr + int64_t(split_of(item)) * nchunk * (CCH * ESZ); };
+    auto w_base = [&](int item) { return wr + int64_t(split_of(item)) * nchunk * wr_chunk; };
     Cursor lc = {tile, 0, act_base(tile)}, wc = {tile, 0, w_base(tile)};
     int w_o0;                 // channel tile the weight offsets were made for
     {
@@ -421,7 +422,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       }
     };
     auto next_weights = [&]() {
-      wc.base += CCH * ESZ;
+      wc.base += wr_chunk;
       if (++wc.chunk == nchunk) {
         wc.chunk = 0;
         if (wc.tile + step < n_tiles) {
@@ -831,11 +832,38 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
           for (int rr = 0; rr < 16; ++rr)
             val[rr] = *reinterpret_cast<const typename TR::acc_t*>(stage + (2 * rr + (lane >> 5)) * RS +
                                                                    (n * 32 + (lane & 31)) * 4);
+          // The block's residual values are all requested before the first result is stored: a
+          // wait for a load also waits for every store issued before it (one counter, in order),
+          // so a load per result, each behind the previous store, costs a round trip per value.
+          if (has_res) {
+            uint32_t addr[16];
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+              const int o = o0 + wo * WOT + m * 32 + 2 * rr + (lane >> 5);
+              addr[rr] = (pos_ok[n] && o < a.O) ? out_base[n] + uint32_t(o) * uint32_t(g.HWo) : 0u;
+            }
+            typename TR::acc_t res[16];
+            if constexpr (__is_same(typename TR::acc_t, int32_t)) {
+#pragma unroll
+              for (int rr = 0; rr < 16; ++rr) res[rr] = static_cast<const int32_t*>(a.residual)[addr[rr]];
+            } else if (odt == GS_F32) {
+#pragma unroll
+              for (int rr = 0; rr < 16; ++rr) res[rr] = static_cast<const float*>(a.residual)[addr[rr]];
+            } else {
+              uint16_t rb[16];
+#pragma unroll
+              for (int rr = 0; rr < 16; ++rr) rb[rr] = static_cast<const uint16_t*>(a.residual)[addr[rr]];
+#pragma unroll
+              for (int rr = 0; rr < 16; ++rr) res[rr] = bf16_bits_to_float(rb[rr]);
+            }
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) val[rr] += res[rr];
+          }
 #pragma unroll
           for (int rr = 0; rr < 16; ++rr) {
             const int o = o0 + wo * WOT + m * 32 + 2 * rr + (lane >> 5);
             if (pos_ok[n] && o < a.O)
-              store_result<typename TR::acc_t>(outp, has_res ? a.residual : nullptr, odt,
+              store_result<typename TR::acc_t>(outp, nullptr, odt,
                                                out_base[n] + uint32_t(o) * uint32_t(g.HWo), val[rr], relu);
           }
         });
