@@ -49,20 +49,20 @@ KERNEL_SOURCES = {
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (26.99e6 + 25.70e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
-    "conv3x3": (14.14e6 + 12.85e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),
-    "conv3x3_b64": (26.99e6 + 25.70e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),
-    "im2col_gather": (12.97e6 + 115.65e6, "windows", "7741b56696f4637c8ca3c5a547f3f4d48b8d1f212974cd69d7997399800e3506"),
-    "maxpool": (103.00e6 + 25.69e6, "reduce", "4b5f1c3525283bcdbdfedb76eecfe0a01ed922a83e0882400e3fedff4fb6d82c"),
-    "reduce": (268.44e6 + 0.52e6, "reduce", "4b5f1c3525283bcdbdfedb76eecfe0a01ed922a83e0882400e3fedff4fb6d82c"),
-    "transpose": (25.82e6 + 25.70e6, "move", "40b347065cd533b906745648d7a7fedda1c39a942e4e6c78a902680868b0b3b9"),
-    "dense_blocked": (50.63e6 + 16.78e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
-    "dense": (1611.42e6 + 281.85e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
-    "mlp_scaled": (28.91e6 + 16.78e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
-    "conv3x3_i8": (7.29e6 + 25.71e6, "conv", "f05183c28ab8462dbb89fd1edff9921d15efdb61b34bf9632b1865d15a5941d5"),
-    "dense_i8": (805.93e6 + 287.46e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
-    "dense_fp8": (806.21e6 + 134.22e6, "gemm", "6181f5b0fabae957816e7b75cf3cbcdc208f1ec28d596f105120f6040b9b355b"),
-    "depthwise": (103.03e6 + 102.76e6, "depthwise", "b55bbabacf3938893acb7ff9df30d54119d03cc82754824aaf4170d2facde200"),
+    "resnet18": (26.99e6 + 25.70e6, "conv", "7eae4cdef1ec0d2406fae62cf9de3dfb4acec277b04eb37b5aa53b2fef5cc340"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
+    "conv3x3": (14.15e6 + 12.85e6, "conv", "7eae4cdef1ec0d2406fae62cf9de3dfb4acec277b04eb37b5aa53b2fef5cc340"),
+    "conv3x3_b64": (26.99e6 + 25.70e6, "conv", "7eae4cdef1ec0d2406fae62cf9de3dfb4acec277b04eb37b5aa53b2fef5cc340"),
+    "im2col_gather": (12.97e6 + 115.65e6, "windows", "28be54f8a8d040349c57db5f9820cda36bffe90e20b1b9dee462b12e92a66d8b"),
+    "maxpool": (103.00e6 + 25.69e6, "reduce", "b45ea8b2d26f14f5a55128314b01ed29d77f86f18a0cd19592276c47d9523874"),
+    "reduce": (268.44e6 + 0.52e6, "reduce", "b45ea8b2d26f14f5a55128314b01ed29d77f86f18a0cd19592276c47d9523874"),
+    "transpose": (25.82e6 + 25.70e6, "move", "3f71ed284b450b94c97176cd729f28061f8fef2f40f28ca8a27bfbf72e4a3d62"),
+    "dense_blocked": (50.63e6 + 16.78e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
+    "dense": (1611.42e6 + 281.85e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
+    "mlp_scaled": (28.91e6 + 16.78e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
+    "conv3x3_i8": (7.30e6 + 25.71e6, "conv", "7eae4cdef1ec0d2406fae62cf9de3dfb4acec277b04eb37b5aa53b2fef5cc340"),
+    "dense_i8": (805.93e6 + 287.46e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
+    "dense_fp8": (806.21e6 + 134.22e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
+    "depthwise": (103.03e6 + 102.76e6, "depthwise", "c9515252f603786f310d6a9178342e1244cdadaa9101f1a1d8b67c2f26904071"),
 }
 
 
