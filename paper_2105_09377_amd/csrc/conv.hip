@@ -22,10 +22,16 @@ namespace gs {
 
 static int conv_max_rows_scan(const ConvArgs& a, int64_t M, int HWo, int TP);
 
-// wr[o][tap][c] = w[o][c][tap] for c < C, zero for C <= c < Cpad.
+// wr[o][tap][c] = w[o][c][tap] for c < C, zero for C <= c < Cpad.  With `wb` (channel counts
+// that are whole chunks, C == Cpad) also the blocked copy (see conv_blocked_weight_offset):
+// element e of 16-byte piece i of block (ob, chunk, tap) is
+// w[ob * 32 + i / 2][chunk * CCH + h * G + e][tap], G = elements in 16 bytes, CCH = 2 G,
+// h = (i % 2) ^ (((r >> 2) ^ (r >> 3)) & 1) with r = i / 2 -- the swizzle the consumers'
+// fragment reads undo; rows past O are zero.
 template <typename T>
 __global__ void __launch_bounds__(256)
-conv_repack_kernel(const T* __restrict__ w, T* __restrict__ wr, int O, int C, int T_, int Cpad) {
+conv_repack_kernel(const T* __restrict__ w, T* __restrict__ wr, T* __restrict__ wb, int O, int C, int T_,
+                   int Cpad) {
   const int64_t total = int64_t(O) * T_ * Cpad;
   for (int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; f < total;
        f += int64_t(gridDim.x) * blockDim.x) {
@@ -34,6 +40,23 @@ conv_repack_kernel(const T* __restrict__ w, T* __restrict__ wr, int O, int C, in
     const int tap = int(ot % T_);
     const int64_t o = ot / T_;
     wr[f] = c < C ? w[(o * C + c) * T_ + tap] : T(0);
+  }
+  if (!wb) return;
+  constexpr int G = 16 / int(sizeof(T)), CCH = 2 * G;
+  const int nchunk = C / CCH;
+  const int64_t total_b = round_up(O, 32) * T_ * C;
+  for (int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; f < total_b;
+       f += int64_t(gridDim.x) * blockDim.x) {
+    const int e = int(f % G);
+    const int i = int((f / G) % 64);
+    const int64_t blk = f / (G * 64);
+    const int tap = int(blk % T_);
+    const int chunk = int((blk / T_) % nchunk);
+    const int64_t ob = blk / T_ / nchunk;
+    const int r = i >> 1, h = (i & 1) ^ (((r >> 2) ^ (r >> 3)) & 1);
+    const int64_t o = ob * 32 + r;
+    const int c = chunk * CCH + h * G + e;
+    wb[f] = o < O ? w[(o * C + c) * T_ + tap] : T(0);
   }
 }
 
@@ -68,57 +91,24 @@ size_t conv_weight_workspace(int in_dtype, int O, int C, int Kh, int Kw) {
                  : conv_weight_front_bytes(in_dtype, O, C, Kh, Kw);
 }
 
-// The blocked copy (see conv_blocked_weight_offset): element e of 16-byte piece i of block
-// (ob, chunk, tap) is w[ob * 32 + i / 2][chunk * CCH + h * G + e][tap], G = elements in 16 bytes,
-// CCH = 2 G, h = (i % 2) ^ (((r >> 2) ^ (r >> 3)) & 1) with r = i / 2 -- the swizzle the
-// consumers' fragment reads undo; rows past O are zero.
-template <typename T>
-__global__ void __launch_bounds__(256)
-conv_repack_blocked_kernel(const T* __restrict__ w, T* __restrict__ wb, int O, int C, int T_) {
-  constexpr int G = 16 / int(sizeof(T)), CCH = 2 * G;
-  const int nchunk = C / CCH;
-  const int64_t total = int64_t(round_up(O, 32)) * T_ * C;
-  for (int64_t f = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; f < total;
-       f += int64_t(gridDim.x) * blockDim.x) {
-    const int e = int(f % G);
-    const int i = int((f / G) % 64);
-    const int64_t blk = f / (G * 64);
-    const int tap = int(blk % T_);
-    const int chunk = int((blk / T_) % nchunk);
-    const int64_t ob = blk / T_ / nchunk;
-    const int r = i >> 1, h = (i & 1) ^ (((r >> 2) ^ (r >> 3)) & 1);
-    const int64_t o = ob * 32 + r;
-    const int c = chunk * CCH + h * G + e;
-    wb[f] = o < O ? w[(o * C + c) * T_ + tap] : T(0);
-  }
-}
-
 hipError_t launch_conv_repack(const void* w, void* wr, int in_dtype, int O, int C, int Kh, int Kw,
                               hipStream_t s) {
   const int Cpad = conv_cpad(in_dtype, C);
-  const int64_t total = int64_t(O) * Kh * Kw * Cpad;
-  if (total == 0) return hipSuccess;
+  const int64_t total = round_up(O, 32) * Kh * Kw * Cpad;   // the longer of the kernel's two loops
+  if (int64_t(O) * Kh * Kw * Cpad == 0) return hipSuccess;
   const int64_t b = ceil_div(total, 256);
   const dim3 grid(unsigned(b < 65536 ? b : 65536));
+  uint8_t* wb = conv_blocked_weight_bytes(in_dtype, O, C, Kh, Kw)
+                    ? static_cast<uint8_t*>(wr) + conv_blocked_weight_offset(in_dtype, O, C, Kh, Kw)
+                    : nullptr;
   if (in_dtype == GS_I8)
     hipLaunchKernelGGL((conv_repack_kernel<uint8_t>), grid, dim3(256), 0, s,
-                       static_cast<const uint8_t*>(w), static_cast<uint8_t*>(wr), O, C, Kh * Kw, Cpad);
+                       static_cast<const uint8_t*>(w), static_cast<uint8_t*>(wr), wb, O, C, Kh * Kw, Cpad);
   else
     hipLaunchKernelGGL((conv_repack_kernel<uint16_t>), grid, dim3(256), 0, s,
-                       static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wr), O, C, Kh * Kw, Cpad);
+                       static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wr),
+                       reinterpret_cast<uint16_t*>(wb), O, C, Kh * Kw, Cpad);
   hipError_t e = hipGetLastError();
-  if (e == hipSuccess && conv_blocked_weight_bytes(in_dtype, O, C, Kh, Kw)) {
-    uint8_t* wb = static_cast<uint8_t*>(wr) + conv_blocked_weight_offset(in_dtype, O, C, Kh, Kw);
-    const int64_t tb = int64_t(round_up(O, 32)) * Kh * Kw * C, bb = ceil_div(tb, 256);
-    const dim3 gb(unsigned(bb < 65536 ? bb : 65536));
-    if (in_dtype == GS_I8)
-      hipLaunchKernelGGL((conv_repack_blocked_kernel<uint8_t>), gb, dim3(256), 0, s,
-                         static_cast<const uint8_t*>(w), wb, O, C, Kh * Kw);
-    else
-      hipLaunchKernelGGL((conv_repack_blocked_kernel<uint16_t>), gb, dim3(256), 0, s,
-                         static_cast<const uint16_t*>(w), reinterpret_cast<uint16_t*>(wb), O, C, Kh * Kw);
-    e = hipGetLastError();
-  }
   if (e == hipSuccess && conv_is_smallc(in_dtype, C))
     e = launch_conv_smallc_pack(w, static_cast<uint8_t*>(wr) + conv_smallc_weight_offset(in_dtype, O, C, Kh, Kw),
                                 in_dtype, O, C, Kh, Kw, s);
