@@ -137,11 +137,15 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
 
   int tile = blockIdx.x;
   if (tile >= n_tiles) return;
-  {  // patch buffers start as zeros: the halo columns are never written again
+  // The patch buffers start as zeros (the halo columns are never written again): every thread
+  // clears its share and all meet at a barrier -- the producers after they have sent off their
+  // first weight transfers and patch loads, which touch other LDS or none and so are under way
+  // while the buffers are cleared.
+  auto clear_patch_buffers = [&]() {
     const i32x4 z = {0, 0, 0, 0};
     for (int off = tid * 16; off < 2 * pbytes; off += 512 * 16) *reinterpret_cast<i32x4*>(pl + off) = z;
-  }
-  __syncthreads();
+    lds_barrier();
+  };
 
   if (producer) {
     // =========================================================================================
@@ -455,6 +459,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
         issue_weights(wc.base, decltype(k_)::value);
         next_weights();
       });
+      clear_patch_buffers();
       wait_vmem<0>();
       lds_barrier();                                     // B0
       int wslot = 0;                                     // LDS weight buffer of the current chunk
@@ -482,6 +487,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
       load_patch(lc.base, d_);
       next_load();
     });
+    clear_patch_buffers();
     store_patch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});   // nothing to clear: the buffers are zero
     next_store();
     load_patch(lc.base, std::integral_constant<int, 0>{});
@@ -521,6 +527,7 @@ __global__ void __launch_bounds__(512) conv_direct4_kernel(ConvArgs a, ConvGeom 
   // A-fragment address inside a 1 KB weight block: row (lane % 32), column lane / 32, swizzled.
   const int afrag = (lane & 31) * 32 + (((lane >> 5) ^ ((((lane & 31) >> 2) ^ ((lane & 31) >> 3)) & 1)) << 4) +
                     wo * (WOT / 32) * 1024;
+  clear_patch_buffers();
   lds_barrier();                                         // B0
   int wslot = 0;
   const bool vec_epi = g.HWo % 4 == 0;
