@@ -49,9 +49,9 @@ KERNEL_SOURCES = {
 # workload -> (fetch + write bytes per launch of its dominant kernel, source group, digest of the
 # sources the counters were taken with)
 TRAFFIC = {
-    "resnet18": (26.99e6 + 25.70e6, "conv", "fe82ca9aa345a4f0ef08a518eefc906c832b04d7ad2a256c5d3920442b654841"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
-    "conv3x3": (14.14e6 + 12.85e6, "conv", "fe82ca9aa345a4f0ef08a518eefc906c832b04d7ad2a256c5d3920442b654841"),
-    "conv3x3_b64": (26.99e6 + 25.70e6, "conv", "fe82ca9aa345a4f0ef08a518eefc906c832b04d7ad2a256c5d3920442b654841"),
+    "resnet18": (26.75e6 + 25.69e6, "conv", "f4748cc2caa3c2531990a0702814e011d54d0b5a9e9a12edc92d73cba98f0991"),       # the stage-1 convolution measured on its own (conv3x3_b64), without the residual every second launch reads
+    "conv3x3": (13.90e6 + 12.85e6, "conv", "f4748cc2caa3c2531990a0702814e011d54d0b5a9e9a12edc92d73cba98f0991"),
+    "conv3x3_b64": (26.75e6 + 25.69e6, "conv", "f4748cc2caa3c2531990a0702814e011d54d0b5a9e9a12edc92d73cba98f0991"),
     "im2col_gather": (12.97e6 + 115.65e6, "windows", "28be54f8a8d040349c57db5f9820cda36bffe90e20b1b9dee462b12e92a66d8b"),
     "maxpool": (103.00e6 + 25.69e6, "reduce", "b45ea8b2d26f14f5a55128314b01ed29d77f86f18a0cd19592276c47d9523874"),
     "reduce": (268.44e6 + 0.52e6, "reduce", "b45ea8b2d26f14f5a55128314b01ed29d77f86f18a0cd19592276c47d9523874"),
@@ -59,7 +59,7 @@ TRAFFIC = {
     "dense_blocked": (50.63e6 + 16.78e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
     "dense": (1611.42e6 + 281.85e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
     "mlp_scaled": (28.91e6 + 16.78e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
-    "conv3x3_i8": (7.31e6 + 25.71e6, "conv", "fe82ca9aa345a4f0ef08a518eefc906c832b04d7ad2a256c5d3920442b654841"),
+    "conv3x3_i8": (7.15e6 + 25.69e6, "conv", "f4748cc2caa3c2531990a0702814e011d54d0b5a9e9a12edc92d73cba98f0991"),
     "dense_i8": (805.93e6 + 287.46e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
     "dense_fp8": (806.21e6 + 134.22e6, "gemm", "26fb4e7e86e567072c495a5931bb5d3a671db0d4bbb0683e7d6380e858d29ee1"),
     "depthwise": (103.03e6 + 102.76e6, "depthwise", "c9515252f603786f310d6a9178342e1244cdadaa9101f1a1d8b67c2f26904071"),
